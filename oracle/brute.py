@@ -1,0 +1,47 @@
+"""Pure-Python brute force of Dual-scope attention for tiny inputs.
+
+TEST INFRASTRUCTURE ONLY.  Written separately from the C oracle and in a
+different shape on purpose (per query, explicit key list, Python floats and
+math.exp), so that the two can be checked against each other.
+
+Definition followed: Section 4.2 (key/value frames of a query = local
+neighbours plus global frames, concatenated) with the per-clip local scope of
+Section 4.1 (own clip plus c_pre / c_post boundary frames).
+"""
+import math
+
+
+def key_frames(a, clip_len, n_clips, w, global_idx):
+    """Frame list seen by a query in frame `a`: local part then global part."""
+    F = clip_len * n_clips
+    clip = a // clip_len
+    first = clip * clip_len - w
+    last = clip * clip_len + clip_len - 1 + w
+    local = [f for f in range(first, last + 1) if 0 <= f < F]
+    return local + [int(g) for g in global_idx]
+
+
+def forward(q, k, v, clip_len, n_clips, w, global_idx, scale=None):
+    """q, k, v: nested lists / arrays indexed [f][p][g][d]. Returns nested lists."""
+    F = clip_len * n_clips
+    P = len(q[0])
+    H = len(q[0][0])
+    D = len(q[0][0][0])
+    if scale is None or scale <= 0:
+        scale = 1.0 / math.sqrt(D)
+    out = [[[[0.0] * D for _ in range(H)] for _ in range(P)] for _ in range(F)]
+    for a in range(F):
+        frames = key_frames(a, clip_len, n_clips, w, global_idx)
+        for p in range(P):
+            for g in range(H):
+                logits = []
+                for f in frames:
+                    logits.append(scale * sum(float(q[a][p][g][d]) * float(k[f][p][g][d])
+                                              for d in range(D)))
+                top = max(logits)
+                ex = [math.exp(x - top) for x in logits]
+                tot = sum(ex)
+                for d in range(D):
+                    out[a][p][g][d] = sum(e * float(v[f][p][g][d])
+                                          for e, f in zip(ex, frames)) / tot
+    return out
