@@ -1,0 +1,158 @@
+/*
+ * dsattn — Dual-scope temporal self-attention for gfx950 (MI355X), C ABI.
+ *
+ * The operation is the DualScope attention of Video-Infinity (arXiv 2406.16260,
+ * Section 4.2) under the clip split of Section 4 / 4.1, with all clips of the
+ * long video resident in one device buffer: the context a clip needs from its
+ * neighbours (c_pre, c_post) and from the whole video (c_global) is gathered by
+ * frame index instead of being exchanged between devices (Section 4.1,
+ * three-round context communication; Appendix, Algorithm 1).
+ *
+ * Notation (the paper's): N clips of F_clip frames, F = N * F_clip; per layer
+ * the latent is [F, H', W', C'] (Section 3), here flattened to [F, P, C] with
+ * P = H' * W' spatial positions and C = heads * head_dim, C fastest, contiguous.
+ * Q, K, V (already projected) and O all have this layout.
+ *
+ * Clip i's key/value frame list ("context list") is
+ *     local  = frames [i*F_clip - w, (i+1)*F_clip + w) intersected with [0, F), ascending
+ *     global = global_idx[0 .. n_global), in the caller's order
+ *     ctx(i) = Concat(local, global)          (duplicates are kept and count twice)
+ * and every query frame of clip i, at every position and head, performs plain
+ * softmax attention (scale * q.k, no mask) over exactly the frames of ctx(i).
+ *
+ * Conventions for every entry point
+ *   - returns DSATTN_OK (0) or a negative dsattn_status; never throws or aborts;
+ *   - pointers marked "host" are host memory, "device" are device memory of the
+ *     plan's device; the caller owns all tensors, the library owns the plan;
+ *   - work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call does not synchronise;
+ *   - arguments are validated before anything is launched.
+ */
+#ifndef DSATTN_H
+#define DSATTN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum dsattn_status {
+    DSATTN_OK = 0,
+    DSATTN_EINVAL = -1,       /* null pointer, non-positive size, index out of range, aliasing */
+    DSATTN_EUNSUPPORTED = -2, /* no kernel for this combination */
+    DSATTN_ENOMEM = -3,       /* host or device allocation failed */
+    DSATTN_EHIP = -4,         /* a HIP runtime call failed; see dsattn_last_error() */
+    DSATTN_ENODEVICE = -5     /* the plan was made host-only (device = -1) */
+} dsattn_status;
+
+typedef enum dsattn_dtype { DSATTN_F32 = 0, DSATTN_BF16 = 1 } dsattn_dtype;
+
+/* dsattn_desc.flags */
+#define DSATTN_FLAG_FORCE_GENERIC 1u /* planner must pick the generic vector-ALU kernel */
+
+/* Problem statement, in the paper's terms. */
+typedef struct dsattn_desc {
+    int32_t clip_len;   /* F_clip >= 1                              (Section 4) */
+    int32_t n_clips;    /* N >= 1; F = N * clip_len                  (Section 4) */
+    int32_t local_ctx;  /* w >= 0: frames taken from each neighbouring side,
+                           |c_pre| = |c_post| = w                    (Section 4.2) */
+    int32_t spatial;    /* P = H' * W' >= 1                          (Section 3) */
+    int32_t heads;      /* h >= 1 */
+    int32_t head_dim;   /* D >= 1; C = h * D */
+    int32_t io_dtype;   /* dsattn_dtype of Q, K, V; accumulation is always fp32 */
+    int32_t out_dtype;  /* dsattn_dtype of O (F32 input requires F32 output) */
+    float scale;        /* softmax scale; <= 0 selects 1/sqrt(D) */
+    uint32_t flags;     /* DSATTN_FLAG_* */
+} dsattn_desc;
+
+typedef struct dsattn_plan_s dsattn_plan_t; /* opaque; made by dsattn_plan() */
+
+/* What the launch planner decided for dsattn_forward (read-only report). */
+typedef struct dsattn_launch_info {
+    int32_t kernel;          /* 0 = generic vector-ALU kernel, 1 = bf16 MFMA streaming kernel */
+    int32_t heads_per_wave;  /* MFMA kernel: heads handled by one wavefront */
+    int32_t local_tiles;     /* MFMA kernel: 16-key tiles covering the local window */
+    int32_t global_tiles;    /* MFMA kernel: 16-key tiles covering the global set */
+    int32_t clips_per_task;  /* consecutive clips walked by one wavefront */
+    int32_t n_tasks;         /* wavefront tasks = grid size */
+    int32_t block_threads;   /* threads per workgroup */
+    int32_t lds_bytes;       /* LDS bytes per workgroup */
+    int64_t algorithmic_bytes; /* Q + K + V read once, O written once */
+} dsattn_launch_info;
+
+/*
+ * Build a plan: validates the descriptor, builds the per-clip context index
+ * table (Section 4.1 c^i; Section 4.2 local + global), picks launch shapes for
+ * this level's (P, h, D) (the latent's H', W', C' vary per U-Net level,
+ * Section 3), and, unless device == -1, uploads the tables to that HIP device.
+ *   global_idx : host, [n_global] int32, each in [0, F); may be NULL iff n_global == 0;
+ *                duplicates and any order are legal.
+ *   device     : HIP device ordinal, or -1 for a host-only plan (index queries only).
+ *   out        : receives the plan; destroy with dsattn_plan_destroy.
+ * Errors: EINVAL, ENOMEM, EHIP.
+ */
+int dsattn_plan(const dsattn_desc *desc, const int32_t *global_idx, int32_t n_global,
+                int device, dsattn_plan_t **out);
+
+/* Frees host and device tables. NULL is allowed. Does not synchronise: the caller
+ * must have finished all work enqueued with this plan. */
+void dsattn_plan_destroy(dsattn_plan_t *plan);
+
+/* lk_max = max over clips of the context list length. */
+int dsattn_plan_ctx_max(const dsattn_plan_t *plan, int32_t *lk_max);
+
+/* Copies the context table to host arrays: ctx_idx [N * lk_max] (-1 padded),
+ * ctx_len [N]. Either may be NULL to skip it. */
+int dsattn_plan_ctx_indices(const dsattn_plan_t *plan, int32_t *ctx_idx, int32_t *ctx_len);
+
+/* Reports the launch planner's choice. */
+int dsattn_plan_launch_info(const dsattn_plan_t *plan, dsattn_launch_info *info);
+
+/*
+ * Context gather (Section 4.1: the context c^i delivered to clip i; Section 4.2:
+ * K = Concat(K_local, K_global), V likewise), materialised:
+ *   Kctx[i][j][p][c] = K[ctx_idx[i][j]][p][c]  for j < ctx_len[i], else 0   (same for V)
+ *   K, V      : device, [F, P, C] of io_dtype
+ *   Kctx, Vctx: device, [N, lk_max, P, C] of io_dtype, written entirely
+ * Either pair (K,Kctx) or (V,Vctx) may be NULL/NULL to skip it.
+ * Errors: EINVAL, ENODEVICE, EHIP.
+ */
+int dsattn_gather_context(const dsattn_plan_t *plan, const void *K, const void *V, void *Kctx,
+                          void *Vctx, void *stream);
+
+/*
+ * Fused Dual-scope attention (Section 4.2), gathering K/V by index from the
+ * original buffers; outputs are concatenated along frames (Section 4.1, v_out).
+ *   Q, K, V : device, [F, P, C] of io_dtype, 16-byte aligned
+ *   O       : device, [F, P, C] of out_dtype, 16-byte aligned, must not overlap Q, K or V
+ * Errors: EINVAL, ENODEVICE, EUNSUPPORTED, EHIP.
+ */
+int dsattn_forward(const dsattn_plan_t *plan, const void *Q, const void *K, const void *V, void *O,
+                   void *stream);
+
+/*
+ * Same attention, consuming the materialised context of dsattn_gather_context:
+ * clip i attends over Kctx[i][0 .. ctx_len[i]).  Runs the generic kernel.
+ */
+int dsattn_forward_ctx(const dsattn_plan_t *plan, const void *Q, const void *Kctx, const void *Vctx,
+                       void *O, void *stream);
+
+/*
+ * Plain device-to-device copy kernel of `bytes` bytes (multiple of 16, both
+ * pointers 16-byte aligned).  Not part of the method: it is the known-traffic
+ * yardstick that achieved bandwidth and profiler byte counters are scaled by.
+ */
+int dsattn_copy_probe(void *dst, const void *src, int64_t bytes, void *stream);
+
+/* Static description of a status code; never NULL. */
+const char *dsattn_strerror(int code);
+
+/* Detail of the calling thread's most recent failure (e.g. the HIP error string);
+ * empty string if none. The pointer stays valid until the thread's next failing call. */
+const char *dsattn_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DSATTN_H */

@@ -1,0 +1,158 @@
+"""CPU-side tests of the C-ABI boundary: exported symbols, argument validation,
+host-only plans and bit-exact context tables against the oracle.  No kernel is launched."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from conftest import ROOT, read_golden_ctx_lists
+from oracle import oracle
+from paper_2406_16260_amd import binding as B
+from paper_2406_16260_amd import synth
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "dsattn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dsattn_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load()
+    names = declared_functions()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def raw_plan(desc_kwargs, gidx, device=-1):
+    lib = B.load()
+    d = dict(clip_len=4, n_clips=2, local_ctx=1, spatial=16, heads=1, head_dim=8,
+             io_dtype=B.DSATTN_F32, out_dtype=B.DSATTN_F32, scale=0.0, flags=0)
+    d.update(desc_kwargs)
+    desc = B.DsattnDesc(**d)
+    g = np.asarray(gidx, dtype=np.int32)
+    h = ctypes.c_void_p()
+    rc = lib.dsattn_plan(ctypes.byref(desc), g.ctypes.data if g.size else None, g.size, device,
+                         ctypes.byref(h))
+    return rc, h
+
+
+@pytest.mark.parametrize("kw,g", [
+    (dict(clip_len=0), [0]), (dict(n_clips=0), [0]), (dict(local_ctx=-1), [0]),
+    (dict(spatial=0), [0]), (dict(heads=0), [0]), (dict(head_dim=0), [0]),
+    (dict(io_dtype=7), [0]), (dict(out_dtype=-1), [0]),
+    (dict(io_dtype=B.DSATTN_F32, out_dtype=B.DSATTN_BF16), [0]),
+    (dict(scale=float("nan")), [0]), (dict(scale=float("inf")), [0]),
+    (dict(), [8]), (dict(), [-1]), (dict(), [0, 3, 99]),
+])
+def test_plan_rejects_bad_arguments(kw, g):
+    rc, h = raw_plan(kw, g)
+    assert rc == B.DSATTN_EINVAL
+    assert not h.value
+    assert B.dsattn_last_error() != ""
+
+
+def test_plan_null_pointers_and_bad_device():
+    lib = B.load()
+    h = ctypes.c_void_p()
+    assert lib.dsattn_plan(None, None, 0, -1, ctypes.byref(h)) == B.DSATTN_EINVAL
+    desc = B.DsattnDesc(4, 2, 1, 16, 1, 8, 0, 0, 0.0, 0)
+    assert lib.dsattn_plan(ctypes.byref(desc), None, 0, -1, None) == B.DSATTN_EINVAL
+    assert lib.dsattn_plan(ctypes.byref(desc), None, 2, -1, ctypes.byref(h)) == B.DSATTN_EINVAL
+    assert lib.dsattn_plan(ctypes.byref(desc), None, -1, -1, ctypes.byref(h)) == B.DSATTN_EINVAL
+    assert lib.dsattn_plan(ctypes.byref(desc), None, 0, -2, ctypes.byref(h)) == B.DSATTN_EINVAL
+    lib.dsattn_plan_destroy(None)  # must be a no-op
+    out = ctypes.c_int32()
+    assert lib.dsattn_plan_ctx_max(None, ctypes.byref(out)) == B.DSATTN_EINVAL
+    assert lib.dsattn_plan_ctx_indices(None, None, None) == B.DSATTN_EINVAL
+    assert lib.dsattn_plan_launch_info(None, None) == B.DSATTN_EINVAL
+
+
+def test_host_only_plan_refuses_device_work():
+    lib = B.load()
+    rc, h = raw_plan({}, [0, 4])
+    assert rc == B.DSATTN_OK and h.value
+    fake = 0x1000  # never dereferenced: validation stops first
+    assert lib.dsattn_forward(h, fake, fake, fake, fake, None) == B.DSATTN_ENODEVICE
+    assert lib.dsattn_forward_ctx(h, fake, fake, fake, fake, None) == B.DSATTN_ENODEVICE
+    assert lib.dsattn_gather_context(h, fake, fake, fake, fake, None) == B.DSATTN_ENODEVICE
+    assert lib.dsattn_forward(h, None, fake, fake, fake, None) == B.DSATTN_EINVAL
+    assert lib.dsattn_forward(None, fake, fake, fake, fake, None) == B.DSATTN_EINVAL
+    lib.dsattn_plan_destroy(h)
+
+
+def test_copy_probe_validates_before_launch():
+    lib = B.load()
+    assert lib.dsattn_copy_probe(None, 0x1000, 64, None) == B.DSATTN_EINVAL
+    assert lib.dsattn_copy_probe(0x1000, 0x2000, 0, None) == B.DSATTN_EINVAL
+    assert lib.dsattn_copy_probe(0x1000, 0x2000, 24, None) == B.DSATTN_EINVAL   # not x16
+    assert lib.dsattn_copy_probe(0x1004, 0x2000, 64, None) == B.DSATTN_EINVAL   # misaligned
+    assert lib.dsattn_copy_probe(0x1000, 0x1010, 64, None) == B.DSATTN_EINVAL   # overlap
+
+
+def test_strerror_is_total():
+    for code in (0, -1, -2, -3, -4, -5, -77, 5):
+        s = B.dsattn_strerror(code)
+        assert isinstance(s, str) and s
+    assert B.dsattn_strerror(0) == "ok"
+
+
+@pytest.mark.parametrize("case", read_golden_ctx_lists())
+def test_plan_ctx_table_matches_hand_derived(case):
+    clip_len, n_clips, w, g, clip, expected = case
+    plan = B.dsattn_plan(clip_len, n_clips, w, 1, 1, 8, g, io_dtype=B.DSATTN_F32, device=-1)
+    idx, ln = B.dsattn_plan_ctx_indices(plan)
+    assert idx[clip, :ln[clip]].tolist() == expected
+    plan.close()
+
+
+@pytest.mark.parametrize("name", ["C0", "C1", "C2", "C3", "C4"])
+def test_plan_ctx_table_bit_exact_vs_oracle_on_workloads(name):
+    wl = synth.WORKLOADS[name]
+    g = synth.global_idx_for(wl)
+    assert len(g) == wl.n_global
+    lv = wl.levels[0]
+    dt = B.DSATTN_F32 if wl.dtype == "f32" else B.DSATTN_BF16
+    plan = B.dsattn_plan(wl.clip_len, wl.n_clips, wl.local_ctx, lv.P, lv.heads, lv.head_dim, g,
+                         io_dtype=dt, device=-1)
+    idx, ln = B.dsattn_plan_ctx_indices(plan)
+    ridx, rln = oracle.ctx_indices(wl.clip_len, wl.n_clips, wl.local_ctx, g)
+    assert B.dsattn_plan_ctx_max(plan) == ridx.shape[1]
+    assert np.array_equal(idx, ridx) and np.array_equal(ln, rln)
+    info = B.dsattn_plan_launch_info(plan)
+    esz = 4 if wl.dtype == "f32" else 2
+    assert info["algorithmic_bytes"] == 4 * wl.F * lv.P * lv.C * esz
+    plan.close()
+
+
+def test_plan_ctx_table_random_shapes_vs_oracle():
+    rng = np.random.default_rng(0)
+    for _ in range(200):
+        clip_len = int(rng.integers(1, 20))
+        n_clips = int(rng.integers(1, 12))
+        w = int(rng.integers(0, 3 * clip_len + 2))
+        F = clip_len * n_clips
+        g = rng.integers(0, F, size=int(rng.integers(0, 9))).astype(np.int32)
+        plan = B.dsattn_plan(clip_len, n_clips, w, 2, 2, 4, g, io_dtype=B.DSATTN_F32, device=-1)
+        idx, ln = B.dsattn_plan_ctx_indices(plan)
+        ridx, rln = oracle.ctx_indices(clip_len, n_clips, w, g)
+        assert np.array_equal(idx, ridx) and np.array_equal(ln, rln)
+        plan.close()
+
+
+def test_workload_recipes():
+    assert synth.stride_global_idx(8, 2).tolist() == [0, 4]
+    assert synth.stride_global_idx(64, 16).tolist() == list(range(0, 64, 4))
+    assert synth.stride_global_idx(2304, 16).tolist() == list(range(0, 2304, 144))
+    g = synth.global_idx_for(synth.WORKLOADS["C4"])
+    assert len(g) == 64 and len(set(g.tolist())) == 64 and (np.diff(g) > 0).all()
+    assert g.min() >= 0 and g.max() < 2304
+    q1 = synth.make_tensor(8, 4, 16, 5, "correlated", "bf16")
+    q2 = synth.make_tensor(8, 4, 16, 5, "correlated", "bf16")
+    assert (q1 == q2).all()
+    # frames are strongly correlated, positions are not
+    x = q1.float()
+    assert (x[0] - x[7]).abs().mean() < 0.3 and (x[:, 0] - x[:, 1]).abs().mean() > 0.5

@@ -1,0 +1,152 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle on the
+same seeded inputs.  Context indices and gathered context are bit-exact; attention outputs
+are within 1e-5 (fp32 path) / 1e-2 (bf16 I/O, fp32 accumulation; see parity_util.assert_parity
+for how bf16 output rounding is accounted)."""
+import numpy as np
+import pytest
+import torch
+
+import parity_util as U
+from oracle import oracle
+from paper_2406_16260_amd import binding as B
+from paper_2406_16260_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def announce(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+def make(F, P, C, seed, gen, dtype):
+    return tuple(synth.make_tensor(F, P, C, seed + t, gen, dtype).to(DEV) for t in range(3))
+
+
+# ---------------------------------------------------------------- C0: the tiny fp32 case
+
+def test_c0_tiny_fp32():
+    wl = synth.WORKLOADS["C0"]
+    lv = wl.levels[0]
+    g = synth.global_idx_for(wl)
+    announce("C0 fp32 2x4 frames 4x4 1x8 w=1 G={0,4} scale=1/sqrt(8)")
+    q, k, v = (t.to(DEV) for t in synth.make_qkv(wl, lv))
+    o, info = U.library_forward(q, k, v, wl.clip_len, wl.n_clips, wl.local_ctx, lv.heads, g,
+                                scale=1.0 / np.sqrt(8.0))
+    ref = U.oracle_forward(q, k, v, wl.clip_len, wl.n_clips, wl.local_ctx, lv.heads, g,
+                           scale=1.0 / np.sqrt(8.0))
+    U.assert_parity(o, ref, "f32_strict", what="C0")
+    assert info["kernel"] == 0  # fp32 runs the vector-ALU kernel
+
+
+# ---------------------------------------------------------------- generic kernel, many shapes
+
+GENERIC_SHAPES = [
+    # clip_len, n_clips, w, P, heads, D, global, dtype
+    (4, 3, 0, 5, 2, 5, [], "f32"),
+    (3, 4, 2, 7, 2, 4, [11, 0, 5], "f32"),
+    (2, 4, 5, 3, 1, 3, [7, 7, 1], "f32"),
+    (5, 1, 3, 2, 1, 6, [2], "f32"),
+    (16, 3, 8, 9, 2, 24, list(range(0, 48, 3)), "f32"),
+    (7, 5, 3, 33, 3, 72, [0, 34, 17, 17], "f32"),       # D > 64: lanes stride over channels
+    (16, 6, 2, 19, 4, 40, list(range(0, 96, 6)), "bf16"),
+    (8, 10, 70, 3, 2, 16, list(range(80)), "bf16"),     # more than 64 keys: lanes stride over keys
+]
+
+
+@pytest.mark.parametrize("shape", GENERIC_SHAPES)
+def test_generic_kernel_matches_oracle(shape):
+    clip_len, n_clips, w, P, h, D, g, dtype = shape
+    announce(f"generic {shape[:6]} G={len(g)} {dtype}")
+    F = clip_len * n_clips
+    q, k, v = make(F, P, h * D, 17, "iid", dtype)
+    for out_dtype in (["f32"] if dtype == "f32" else ["f32", "bf16"]):
+        o, info = U.library_forward(q, k, v, clip_len, n_clips, w, h, g, out_dtype=out_dtype,
+                                    flags=B.DSATTN_FLAG_FORCE_GENERIC)
+        assert info["kernel"] == 0
+        ref = U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g)
+        U.assert_parity(o, ref, "f32_strict" if dtype == "f32" else out_dtype, what=str(shape))
+
+
+# ---------------------------------------------------------------- gather: bit exact
+
+@pytest.mark.parametrize("shape", [
+    (4, 2, 1, 16, 8, [0, 4], "f32"),
+    (16, 4, 2, 40, 320, list(range(0, 64, 4)), "bf16"),
+    (3, 5, 4, 3, 5, [14, 2], "bf16"),      # slab of 30 bytes: element-wise path
+    (2, 3, 0, 1, 3, [], "f32"),            # slab of 12 bytes
+    (4, 3, 9, 6, 8, [], "bf16"),           # edge clips shorter than lk_max: zero-filled rows
+])
+def test_gather_context_bit_exact(shape):
+    clip_len, n_clips, w, P, C, g, dtype = shape
+    announce(f"gather {shape[:5]} G={len(g)} {dtype}")
+    F = clip_len * n_clips
+    k, v, _ = make(F, P, C, 3, "iid", dtype)
+    plan = B.dsattn_plan(clip_len, n_clips, w, P, 1, C, g, io_dtype=U.dt_code(dtype), device=0)
+    lk = B.dsattn_plan_ctx_max(plan)
+    idx, ln = B.dsattn_plan_ctx_indices(plan)
+    ridx, rln = oracle.ctx_indices(clip_len, n_clips, w, g)
+    assert np.array_equal(idx, ridx) and np.array_equal(ln, rln)
+    kc = torch.full((n_clips, lk, P, C), 7.0, dtype=k.dtype, device=DEV)
+    vc = torch.full((n_clips, lk, P, C), 7.0, dtype=k.dtype, device=DEV)
+    B.dsattn_gather_context(plan, k, v, kc, vc)
+    torch.cuda.synchronize()
+    as_bits = (lambda t: t.cpu().view(torch.int16).numpy()) if dtype == "bf16" else \
+              (lambda t: t.cpu().view(torch.int32).numpy())
+    for src, dst in ((k, kc), (v, vc)):
+        ref = oracle.gather_context(as_bits(src), clip_len, n_clips, w, g)
+        assert np.array_equal(as_bits(dst), ref)
+    # one pair at a time is allowed
+    kc2 = torch.zeros_like(kc)
+    B.dsattn_gather_context(plan, k, None, kc2, None)
+    torch.cuda.synchronize()
+    assert torch.equal(kc2, kc)
+    plan.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_forward_ctx_equals_forward(dtype):
+    clip_len, n_clips, w, P, h, D = 8, 4, 3, 11, 2, 16
+    g = [31, 0, 9, 9]
+    announce(f"forward_ctx {dtype}")
+    F = clip_len * n_clips
+    q, k, v = make(F, P, h * D, 29, "iid", dtype)
+    plan = B.dsattn_plan(clip_len, n_clips, w, P, h, D, g, io_dtype=U.dt_code(dtype),
+                         out_dtype=B.DSATTN_F32, flags=B.DSATTN_FLAG_FORCE_GENERIC, device=0)
+    lk = B.dsattn_plan_ctx_max(plan)
+    kc = torch.empty((n_clips, lk, P, h * D), dtype=k.dtype, device=DEV)
+    vc = torch.empty_like(kc)
+    B.dsattn_gather_context(plan, k, v, kc, vc)
+    o1 = torch.empty((F, P, h * D), dtype=torch.float32, device=DEV)
+    o2 = torch.empty_like(o1)
+    B.dsattn_forward(plan, q, k, v, o1)
+    B.dsattn_forward_ctx(plan, q, kc, vc, o2)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2)   # same kernel, same order of operations
+    ref = U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g)
+    U.assert_parity(o2, ref, "f32_strict" if dtype == "f32" else "f32", what="forward_ctx")
+    plan.close()
+
+
+def test_device_argument_checks():
+    lib = B.load()
+    plan = B.dsattn_plan(4, 2, 1, 16, 1, 8, [0, 4], io_dtype=B.DSATTN_F32, device=0)
+    x = torch.zeros((8, 16, 8), device=DEV)
+    o = torch.zeros_like(x)
+    st = torch.cuda.current_stream().cuda_stream
+    assert lib.dsattn_forward(plan.handle, x.data_ptr(), x.data_ptr(), x.data_ptr(),
+                              x.data_ptr(), st) == B.DSATTN_EINVAL          # O aliases Q
+    assert lib.dsattn_forward(plan.handle, x.data_ptr() + 4, x.data_ptr(), x.data_ptr(),
+                              o.data_ptr(), st) == B.DSATTN_EINVAL          # misaligned
+    assert lib.dsattn_forward(plan.handle, x.data_ptr(), x.data_ptr(), x.data_ptr(),
+                              o.data_ptr(), st) == B.DSATTN_OK              # K may alias Q
+    torch.cuda.synchronize()
+    plan.close()
+
+
+def test_copy_probe_copies():
+    src = torch.arange(1 << 20, dtype=torch.int32, device=DEV)
+    dst = torch.zeros_like(src)
+    B.dsattn_copy_probe(dst, src, src.numel() * 4)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
