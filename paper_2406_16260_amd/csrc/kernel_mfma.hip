@@ -1,425 +1,29 @@
-// bf16 MFMA streaming kernel for Dual-scope temporal attention on gfx950 (Section 4.2 of the
-// paper: keys/values of a clip = Concat(local frames, global frames); clip length 16).
-//
-// Work decomposition.  One wavefront (= one 64-thread workgroup) owns a "row group": one
-// spatial position and HPW consecutive heads, whose channels are HPW*D contiguous bf16 per
-// frame, and walks M consecutive clips of that row group in frame order.
-//   * Global K/V (G frames) are loaded once per task and kept in registers, already in MFMA
-//     operand form.
-//   * Local K/V live in an LDS ring of R = 16 + 2w frame rows.  Clip i needs frames
-//     [16i - w, 16i + 16 + w); stepping to clip i+1 replaces exactly the 16 oldest rows, so
-//     every own frame of the chunk is read from HBM once and the boundary frames shared with
-//     the neighbouring clips (c_pre / c_post of Section 4.1) are reused on chip.
-//   * The next clip's Q/K/V rows are in flight in registers while the current clip is computed.
-// Per clip and head:  S^T = K Q^T  (16x16x32 bf16 MFMA, keys on M, the 16 query frames on N),
-// fp32 softmax over keys (in-lane plus two cross-lane steps), P^T rounded to bf16 and fed
-// straight back as the B operand of  O^T = V^T P^T  (16x16x16 bf16 MFMA).  V^T operands are made
-// from row-major V rows with an MFMA against a 0/1 selector matrix, which is exact.
-//
-// No barrier couples wavefronts; LDS regions are private to the wavefront.
-#include <hip/hip_runtime.h>
-
+// Host side of the bf16 MFMA streaming kernel: variant lookup, the launch planner's choices
+// for it (heads per wavefront, wavefronts per workgroup, clips per chunk) and the launcher.
 #include <algorithm>
+#include <cmath>
 #include <cstdlib>
 
+#include "mfma_kernel.h"
 #include "plan.h"
 
 namespace dsattn {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-struct MfmaArgs {
-    const __bf16 *Q, *K, *V;
-    void *O;
-    const int32_t *gidx;  // device [G]
-    int32_t N, F, P, h, w, G, R;
-    int32_t M;       // clips per task
-    int32_t NC;      // chunks per row group
-    int32_t RG;      // row groups = P * h / HPW
-    int32_t T;       // tasks = RG * NC
-    int64_t FS;      // frame stride in elements = P * C
-    int32_t C;
-    float sc;        // scale * log2(e)
-};
-
-// LDS row stride in bytes for a row of SEG bf16: padded so that consecutive rows start 4 banks
-// apart modulo 8 (16-byte reads of 8 consecutive rows then touch all 32 banks once).
-__host__ __device__ constexpr int row_stride_bytes(int seg)
-{
-    return ((seg / 2 + 4) % 8 == 4) ? seg * 2 + 16 : seg * 2 + 32;
-}
-
-// Orders LDS accesses of the wavefront's lanes: LDS operations of one wavefront execute in
-// issue order, so only the compiler has to be kept from moving them.
-__device__ __forceinline__ void wave_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-}
-
-template <int D, int HPW, int NLT, int NGT, bool OUT_F32>
-__global__ __launch_bounds__(64, 2) void dsattn_mfma_kernel(const MfmaArgs a)
-{
-    constexpr int SEG = D * HPW;          // bf16 per frame row of this row group
-    constexpr int NCH = SEG / 8;          // 16-byte chunks per row
-    constexpr int NLD = (NCH + 3) / 4;    // 64-lane load instructions per 16-row tile
-    constexpr int RS = row_stride_bytes(SEG);
-    constexpr int NKB = (D + 31) / 32;    // 32-wide contraction blocks of QK^T
-    constexpr int NDT = (D + 15) / 16;    // 16-row tiles of O^T
-    constexpr int DCH = D / 8;            // chunks per head
-    constexpr int NT = NLT + NGT;
-    static_assert(D % 8 == 0, "head_dim must be a multiple of 8");
-
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int R = a.R;
-    unsigned char *kring = smem;
-    unsigned char *vring = smem + R * RS;
-    unsigned char *qo = smem + 2 * R * RS;
-
-    const int lane = threadIdx.x;
-    const int l16 = lane & 15;  // MFMA row (A) / column (B, C) index
-    const int lg = lane >> 4;   // MFMA k-group (A, B) / row-group (C) index
-
-    // ---- task decode; consecutive hardware workgroup ids go round-robin over the 8 XCDs, so
-    // give each XCD a contiguous range of logical tasks (neighbouring rows share cache lines).
-    int t = blockIdx.x;
-    {
-        const int per = a.T >> 3;
-        if (t < (per << 3)) t = (t & 7) * per + (t >> 3);
-    }
-    const int ck = t / a.RG;
-    const int rg = t - ck * a.RG;
-    const int hg = a.h / HPW;
-    const int p = rg / hg;
-    const int g0 = (rg - p * hg) * HPW;
-    const int64_t rowoff = (int64_t)p * a.C + (int64_t)g0 * D;
-    const int c0 = ck * a.M;
-    const int c1 = min(a.N, c0 + a.M);
-    const int w = a.w;
-    const int F = a.F;
-    const int64_t FS = a.FS;
-
-    const unsigned char *Qb = (const unsigned char *)(a.Q + rowoff);
-    const unsigned char *Kb = (const unsigned char *)(a.K + rowoff);
-    const unsigned char *Vb = (const unsigned char *)(a.V + rowoff);
-    const int64_t FSB = FS * 2;  // frame stride in bytes
-
-    // per-lane load geometry: lane-load `r` covers tile row fq(r), 16-byte chunk cq(r);
-    // voff = byte offset from the tile's first frame row, loff = byte offset in a 16-row LDS tile
-    constexpr bool kFullTile = (16 * NCH) % 64 == 0;  // every lane of every load is in the tile
-    uint32_t voff[NLD], loff[NLD];
-    int fq[NLD];
-#pragma unroll
-    for (int r = 0; r < NLD; ++r) {
-        const int idx = lane + 64 * r;
-        fq[r] = idx / NCH;
-        const int cq = idx - fq[r] * NCH;
-        voff[r] = (uint32_t)fq[r] * (uint32_t)FSB + (uint32_t)cq * 16u;
-        loff[r] = (uint32_t)(fq[r] * RS + cq * 16);
-    }
-    auto in_tile = [&](int r) __attribute__((always_inline)) -> bool {
-        return kFullTile || lane + 64 * r < 16 * NCH;
-    };
-
-    // 16 consecutive frames starting at frame0 (wave-uniform); rows >= nrows and frames
-    // outside [0, F) give zeros
-    auto load_rows = [&](const unsigned char *base, int frame0, int nrows, uint4(&st)[NLD])
-                         __attribute__((always_inline)) {
-        const unsigned char *tb = base + (int64_t)frame0 * FSB;
-        if (kFullTile && nrows == 16 && frame0 >= 0 && frame0 + 16 <= F) {
-#pragma unroll
-            for (int r = 0; r < NLD; ++r) st[r] = *(const uint4 *)(tb + voff[r]);
-        } else {
-#pragma unroll
-            for (int r = 0; r < NLD; ++r) {
-                const int f = frame0 + fq[r];
-                const bool ok = in_tile(r) && fq[r] < nrows && f >= 0 && f < F;
-                uint4 x = make_uint4(0, 0, 0, 0);
-                if (ok) x = *(const uint4 *)(tb + (int64_t)fq[r] * FSB + (voff[r] - (uint32_t)fq[r] * (uint32_t)FSB));
-                st[r] = x;
-            }
-        }
-    };
-    // tile rows to LDS rows (slot0 + fq) mod ring of `buf`
-    auto store_rows = [&](unsigned char *buf, int slot0, int nrows, int ring,
-                          const uint4(&st)[NLD]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int r = 0; r < NLD; ++r) {
-            int wrap = (slot0 + fq[r] >= ring) ? ring : 0;
-            if (in_tile(r) && fq[r] < nrows)
-                *(uint4 *)(buf + (slot0 - wrap) * RS + loff[r]) = st[r];
-        }
-    };
-
-    // A/B operand of the 16x16x32 MFMA: row `row` of an LDS tile, head `hh`, block `kb`
-    auto read_op32 = [&](const unsigned char *buf, int row, int hh, int kb)
-                         __attribute__((always_inline)) -> bf16x8 {
-        const int ch = 4 * kb + lg;  // chunk within the head
-        uint4 x = make_uint4(0, 0, 0, 0);
-        if (4 * kb + 3 < DCH || ch < DCH) x = *(const uint4 *)(buf + row * RS + (hh * DCH + ch) * 16);
-        return __builtin_bit_cast(bf16x8, x);
-    };
-
-    // 0/1 selector operands: sel[hf] picks channels 16*hf .. 16*hf+15 of a 32-wide block
-    bf16x8 sel[2];
-#pragma unroll
-    for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-            sel[hf][e] = (8 * lg + e == 16 * hf + l16) ? (__bf16)1.0f : (__bf16)0.0f;
-
-    // V^T operand (A of the 16x16x16 MFMA) for channels 16*(2kb+hf) .. +15 from the V operand
-    // `av` (16 keys x 32 channels): an exact transpose through the matrix core
-    auto vt_from = [&](const bf16x8 av, int hf) __attribute__((always_inline)) -> s16x4 {
-        f32x4 z = {0.f, 0.f, 0.f, 0.f};
-        z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, sel[hf], z, 0, 0, 0);
-        bf16x4 b;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) b[e] = (__bf16)z[e];  // exact: z holds bf16 values
-        return __builtin_bit_cast(s16x4, b);
-    };
-
-    // ---- global context: registers, MFMA operand form
-    bf16x8 kg[NGT > 0 ? NGT : 1][HPW][NKB];
-    s16x4 vgt[NGT > 0 ? NGT : 1][HPW][NDT];
-    uint4 stQ[NLD], stK[NLD], stV[NLD];
-#pragma unroll
-    for (int tg = 0; tg < NGT; ++tg) {
-#pragma unroll
-        for (int r = 0; r < NLD; ++r) {
-            const int j = 16 * tg + fq[r];
-            stK[r] = make_uint4(0, 0, 0, 0);
-            stV[r] = make_uint4(0, 0, 0, 0);
-            if (in_tile(r) && j < a.G) {
-                const int64_t goff = (int64_t)a.gidx[j] * FSB + (voff[r] - (uint32_t)fq[r] * (uint32_t)FSB);
-                stK[r] = *(const uint4 *)(Kb + goff);
-                stV[r] = *(const uint4 *)(Vb + goff);
-            }
-        }
-        wave_sync();
-        store_rows(kring, 0, 16, 16, stK);
-        store_rows(vring, 0, 16, 16, stV);
-        wave_sync();
-#pragma unroll
-        for (int hh = 0; hh < HPW; ++hh) {
-#pragma unroll
-            for (int kb = 0; kb < NKB; ++kb) {
-                kg[tg][hh][kb] = read_op32(kring, l16, hh, kb);
-                const bf16x8 av = read_op32(vring, l16, hh, kb);
-#pragma unroll
-                for (int hf = 0; hf < 2; ++hf)
-                    if (2 * kb + hf < NDT) vgt[tg][hh][2 * kb + hf] = vt_from(av, hf);
-            }
-        }
-    }
-    wave_sync();
-
-    // ---- prime the ring with the 2w frames that precede the first bulk tile
-#pragma unroll
-    for (int tl = 0; tl + 1 < NLT; ++tl) {
-        const int nrows = min(16, 2 * w - 16 * tl);
-        if (nrows > 0) {
-            const int f0 = 16 * c0 - w + 16 * tl;
-            load_rows(Kb, f0, nrows, stK);
-            load_rows(Vb, f0, nrows, stV);
-            const int s0 = (16 * c0 + 16 * tl) % R;  // slot of frame f is (f + w) mod R
-            store_rows(kring, s0, nrows, R, stK);
-            store_rows(vring, s0, nrows, R, stV);
-        }
-    }
-
-    // first bulk tile: Q frames [16 c0, +16), K/V frames [16 c0 + w, +16)
-    load_rows(Qb, 16 * c0, 16, stQ);
-    load_rows(Kb, 16 * c0 + w, 16, stK);
-    load_rows(Vb, 16 * c0 + w, 16, stV);
-
-    int s_bulk = (16 * c0 + 2 * w) % R;  // ring slot of the bulk tile's first row
-    int b0 = (16 * c0) % R;              // ring slot of the window's first frame (16 i - w)
-
-    for (int i = c0; i < c1; ++i) {
-        wave_sync();
-        store_rows(qo, 0, 16, 16, stQ);
-        store_rows(kring, s_bulk, 16, R, stK);
-        store_rows(vring, s_bulk, 16, R, stV);
-        if (i + 1 < c1) {
-            load_rows(Qb, 16 * (i + 1), 16, stQ);
-            load_rows(Kb, 16 * (i + 1) + w, 16, stK);
-            load_rows(Vb, 16 * (i + 1) + w, 16, stV);
-        }
-        wave_sync();
-
-        // validity of this lane's local keys: C/D row 4*lg + e of local tile tl is ring slot
-        // 16 tl + 4 lg + e, holding frame 16 i - w + ((slot - b0) mod R)
-        bool lvalid[NLT][4];
-        int arow[NLT];  // ring row this lane feeds as MFMA row l16 of local tile tl (clamped)
-        const bool interior = 16 * i - w >= 0 && 16 * i + 16 + w <= F;
-#pragma unroll
-        for (int tl = 0; tl < NLT; ++tl) {
-            arow[tl] = min(16 * tl + l16, R - 1);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int s = 16 * tl + 4 * lg + e;
-                bool ok = s < R;
-                if (!interior) {
-                    int rel = s - b0;
-                    if (rel < 0) rel += R;
-                    const int f = 16 * i - w + rel;
-                    ok = ok && f >= 0 && f < F;
-                }
-                lvalid[tl][e] = ok;
-            }
-        }
-
-#pragma unroll
-        for (int hh = 0; hh < HPW; ++hh) {
-            // ---- S^T = K Q^T for all key tiles
-            f32x4 s[NT];
-#pragma unroll
-            for (int tt = 0; tt < NT; ++tt) s[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kb = 0; kb < NKB; ++kb) {
-                const bf16x8 qop = read_op32(qo, l16, hh, kb);
-#pragma unroll
-                for (int tg = 0; tg < NGT; ++tg)
-                    s[tg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kg[tg][hh][kb], qop, s[tg], 0, 0,
-                                                                    0);
-#pragma unroll
-                for (int tl = 0; tl < NLT; ++tl) {
-                    const bf16x8 ak = read_op32(kring, arow[tl], hh, kb);
-                    s[NGT + tl] =
-                        __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak, qop, s[NGT + tl], 0, 0, 0);
-                }
-            }
-
-            // ---- softmax over keys, per query column (fp32)
-            float mx = -INFINITY;
-#pragma unroll
-            for (int tg = 0; tg < NGT; ++tg)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float x = (16 * tg + 4 * lg + e < a.G) ? s[tg][e] * a.sc : -INFINITY;
-                    s[tg][e] = x;
-                    mx = fmaxf(mx, x);
-                }
-#pragma unroll
-            for (int tl = 0; tl < NLT; ++tl)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float x = lvalid[tl][e] ? s[NGT + tl][e] * a.sc : -INFINITY;
-                    s[NGT + tl][e] = x;
-                    mx = fmaxf(mx, x);
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            float lsum = 0.f;
-            s16x4 pt[NT];
-#pragma unroll
-            for (int tt = 0; tt < NT; ++tt) {
-                bf16x4 pb;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    pb[e] = (__bf16)__builtin_amdgcn_exp2f(s[tt][e] - mx);  // RNE to bf16
-                    lsum += (float)pb[e];  // denominator from the rounded weights
-                }
-                pt[tt] = __builtin_bit_cast(s16x4, pb);
-            }
-            lsum += __shfl_xor(lsum, 16);
-            lsum += __shfl_xor(lsum, 32);
-            const float inv = 1.0f / lsum;
-
-            // ---- O^T = V^T P^T
-            f32x4 o[NDT];
-#pragma unroll
-            for (int dt = 0; dt < NDT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int tg = 0; tg < NGT; ++tg)
-#pragma unroll
-                for (int dt = 0; dt < NDT; ++dt)
-                    o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vgt[tg][hh][dt], pt[tg], o[dt],
-                                                                     0, 0, 0);
-#pragma unroll
-            for (int tl = 0; tl < NLT; ++tl)
-#pragma unroll
-                for (int kb = 0; kb < NKB; ++kb) {
-                    const bf16x8 av = read_op32(vring, arow[tl], hh, kb);
-#pragma unroll
-                    for (int hf = 0; hf < 2; ++hf) {
-                        const int dt = 2 * kb + hf;
-                        if (dt < NDT)
-                            o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
-                                vt_from(av, hf), pt[NGT + tl], o[dt], 0, 0, 0);
-                    }
-                }
-
-            // ---- normalise; lane holds channels 16 dt + 4 lg + {0..3} of query frame l16
-            if constexpr (OUT_F32) {
-                float *Ob = (float *)a.O + rowoff + (int64_t)(16 * i + l16) * FS + hh * D;
-#pragma unroll
-                for (int dt = 0; dt < NDT; ++dt) {
-                    const int d = 16 * dt + 4 * lg;
-                    if (16 * dt + 15 < D || d < D) {
-                        f32x4 y = o[dt] * inv;
-                        *(f32x4 *)(Ob + d) = y;
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int dt = 0; dt < NDT; ++dt) {
-                    const int d = 16 * dt + 4 * lg;
-                    if (16 * dt + 15 < D || d < D) {
-                        bf16x4 y;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) y[e] = (__bf16)(o[dt][e] * inv);
-                        *(bf16x4 *)(qo + l16 * RS + (hh * D + d) * 2) = y;
-                    }
-                }
-            }
-        }
-
-        if constexpr (!OUT_F32) {
-            // ---- O rows back out of LDS as full 16-byte lanes, coalesced along channels
-            wave_sync();
-            unsigned char *Ob = (unsigned char *)((__bf16 *)a.O + rowoff) + (int64_t)(16 * i) * FSB;
-#pragma unroll
-            for (int r = 0; r < NLD; ++r)
-                if (in_tile(r)) *(uint4 *)(Ob + voff[r]) = *(const uint4 *)(qo + loff[r]);
-        }
-
-        s_bulk += 16;
-        if (s_bulk >= R) s_bulk -= R;
-        b0 += 16;
-        if (b0 >= R) b0 -= R;
-    }
-}
-
-// ------------------------------------------------------------------ host side
-
 namespace {
 
-struct Variant {
-    int D, HPW, NLT, NGT;
-    bool out_f32;
-    const void *fn;
-};
+constexpr int kLdsPerCu = 160 * 1024;  // gfx950 LDS per compute unit, also the per-workgroup cap
+constexpr int kCus = 256;
 
-#define DSATTN_V(D, HPW, NLT, NGT)                                                       \
-    {D, HPW, NLT, NGT, false, (const void *)&dsattn_mfma_kernel<D, HPW, NLT, NGT, false>}, \
-    {D, HPW, NLT, NGT, true, (const void *)&dsattn_mfma_kernel<D, HPW, NLT, NGT, true>}
-
-const Variant kVariants[] = {
-    DSATTN_V(160, 1, 2, 0),
-    DSATTN_V(160, 1, 2, 1),
-};
-#undef DSATTN_V
-
-const Variant *find_variant(int D, int HPW, int NLT, int NGT, bool out_f32)
+const MfmaVariant *find_variant(int D, int HPW, int NLT, int NGT, bool out_f32)
 {
-    for (const Variant &v : kVariants)
-        if (v.D == D && v.HPW == HPW && v.NLT == NLT && v.NGT == NGT && v.out_f32 == out_f32)
-            return &v;
+    int n = 0;
+    const MfmaVariant *v = nullptr;
+    if (D == 160) v = mfma_variants_d160(&n);
+    else if (D == 80) v = mfma_variants_d80(&n);
+    else if (D == 40) v = mfma_variants_d40(&n);
+    for (int i = 0; i < n; ++i)
+        if (v[i].HPW == HPW && v[i].NLT == NLT && v[i].NGT == NGT && v[i].out_f32 == out_f32)
+            return &v[i];
     return nullptr;
 }
 
@@ -441,39 +45,56 @@ bool mfma_plan(dsattn_plan_t &pl)
     const int R = 16 + 2 * d.local_ctx;
     const int NLT = (R + 15) / 16;
     const bool out_f32 = d.out_dtype == DSATTN_F32;
-    // heads per wave: prefer 160 contiguous channels per row
-    int hpw = 0;
+
+    // heads per wavefront: the widest variant that exists for this head_dim (long contiguous
+    // rows per frame); a wavefront never straddles two positions
+    const MfmaVariant *var = nullptr;
     for (int cand : {4, 2, 1})
-        if (d.heads % cand == 0 && find_variant(d.head_dim, cand, NLT, NGT, out_f32)) {
-            hpw = cand;
+        if (d.heads % cand == 0 && (var = find_variant(d.head_dim, cand, NLT, NGT, out_f32)))
+            break;
+    if (!var) return false;
+    const int hpw = var->HPW;
+    const int lds_wave = (2 * R + 16) * row_stride_bytes(d.head_dim * hpw);
+    if (lds_wave > kLdsPerCu) return false;
+    const int RG = d.spatial * (d.heads / hpw);
+
+    // wavefronts per workgroup: as many neighbouring row groups as LDS and the register budget
+    // allow (their rows are contiguous in memory and are fetched together)
+    const int max_waves_cu = std::min(4 * var->WPE, kLdsPerCu / lds_wave);
+    int wpb = 1;
+    for (int cand : {8, 4, 2, 1})
+        if (cand <= max_waves_cu && RG % cand == 0) {
+            wpb = cand;
             break;
         }
-    if (!hpw) return false;
-    const int seg = d.head_dim * hpw;
-    const int lds = (2 * R + 16) * row_stride_bytes(seg);
-    if (lds > 160 * 1024) return false;
+    {
+        const int e = env_int("DSATTN_WAVES_PER_BLOCK", wpb);
+        if (e >= 1 && e <= 8 && e <= max_waves_cu && RG % e == 0) wpb = e;
+    }
+    const int blocks_cu = std::max(1, max_waves_cu / wpb);
+    const int bpc = RG / wpb;
 
-    // clips per task: trade re-reads of context at chunk starts against filling the machine
-    const int RG = d.spatial * (d.heads / hpw);
-    const int waves_per_cu = std::max(1, std::min(8, (160 * 1024) / lds));
-    const double slots = 256.0 * waves_per_cu;
-    int best_m = d.n_clips;
+    // chunks per row group: more chunks fill the machine and shorten the tail, fewer chunks
+    // re-read less context (2w boundary frames + G global frames per chunk)
+    const double slots = (double)kCus * blocks_cu;
+    int best_nc = 1;
     double best_cost = 1e300;
-    for (int m = 1; m <= d.n_clips; ++m) {
-        const int nc = (d.n_clips + m - 1) / m;
-        const double tasks = (double)RG * nc;
-        const double rounds = std::ceil(tasks / slots);
-        const double fill = rounds * slots / tasks;
+    for (int nc = 1; nc <= d.n_clips; ++nc) {
+        const int m = (d.n_clips + nc - 1) / nc;
+        if ((d.n_clips + m - 1) / m != nc) continue;  // same chunking as a smaller nc
+        const double blocks = (double)bpc * nc;
+        const double rounds = std::ceil(blocks / slots);
+        const double fill = rounds * slots / blocks;
         const double kv = (16.0 * m + (nc > 1 ? 2.0 * d.local_ctx : 0.0) + G) / (16.0 * m);
-        const double traffic = (2.0 + 2.0 * kv) / 4.0;
-        const double cost = traffic * fill;
+        const double cost = (2.0 + 2.0 * kv) / 4.0 * fill;
         if (cost < best_cost - 1e-12) {
             best_cost = cost;
-            best_m = m;
+            best_nc = nc;
         }
     }
-    best_m = std::max(1, std::min(d.n_clips, env_int("DSATTN_CLIPS_PER_TASK", best_m)));
-    const int NC = (d.n_clips + best_m - 1) / best_m;
+    int m = (d.n_clips + best_nc - 1) / best_nc;
+    m = std::max(1, std::min(d.n_clips, env_int("DSATTN_CLIPS_PER_TASK", m)));
+    const int NC = (d.n_clips + m - 1) / m;
     if ((int64_t)RG * NC > 0x7fffffffLL) return false;
 
     dsattn_launch_info &li = pl.launch;
@@ -481,10 +102,10 @@ bool mfma_plan(dsattn_plan_t &pl)
     li.heads_per_wave = hpw;
     li.local_tiles = NLT;
     li.global_tiles = NGT;
-    li.clips_per_task = best_m;
+    li.clips_per_task = m;
     li.n_tasks = RG * NC;
-    li.block_threads = 64;
-    li.lds_bytes = lds;
+    li.block_threads = 64 * wpb;
+    li.lds_bytes = lds_wave * wpb;
     return true;
 }
 
@@ -493,9 +114,10 @@ hipError_t launch_mfma(const dsattn_plan_t &pl, const void *Q, const void *K, co
 {
     const dsattn_desc &d = pl.desc;
     const dsattn_launch_info &li = pl.launch;
-    const Variant *v = find_variant(d.head_dim, li.heads_per_wave, li.local_tiles, li.global_tiles,
-                                    d.out_dtype == DSATTN_F32);
+    const MfmaVariant *v = find_variant(d.head_dim, li.heads_per_wave, li.local_tiles,
+                                        li.global_tiles, d.out_dtype == DSATTN_F32);
     if (!v) return hipErrorInvalidValue;
+    const int wpb = li.block_threads / 64;
 
     MfmaArgs a;
     a.Q = (const __bf16 *)Q;
@@ -505,18 +127,21 @@ hipError_t launch_mfma(const dsattn_plan_t &pl, const void *Q, const void *K, co
     a.gidx = pl.d_global_idx;
     a.N = d.n_clips;
     a.F = pl.F;
-    a.P = d.spatial;
     a.h = d.heads;
     a.w = d.local_ctx;
     a.G = (int32_t)pl.global_idx.size();
     a.R = 16 + 2 * d.local_ctx;
     a.M = li.clips_per_task;
-    a.NC = (d.n_clips + a.M - 1) / a.M;
     a.RG = d.spatial * (d.heads / li.heads_per_wave);
-    a.T = li.n_tasks;
-    a.FS = (int64_t)d.spatial * pl.C;
+    a.BPC = a.RG / wpb;
     a.C = pl.C;
+    a.FS = (int64_t)d.spatial * pl.C;
     a.sc = pl.scale * 1.4426950408889634f;
+
+    // the grid must be exactly chunks x workgroups-per-chunk, each workgroup wpb whole row groups
+    const int NC = (d.n_clips + a.M - 1) / a.M;
+    if (a.RG % wpb != 0 || (int64_t)a.BPC * NC * wpb != (int64_t)li.n_tasks)
+        return hipErrorInvalidValue;
 
     if (li.lds_bytes > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(v->fn, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -524,8 +149,8 @@ hipError_t launch_mfma(const dsattn_plan_t &pl, const void *Q, const void *K, co
         if (e != hipSuccess) return e;
     }
     void *params[] = {&a};
-    return hipLaunchKernel(v->fn, dim3((unsigned)li.n_tasks), dim3(64), params,
-                           (size_t)li.lds_bytes, st);
+    return hipLaunchKernel(v->fn, dim3((unsigned)(a.BPC * NC)), dim3((unsigned)li.block_threads),
+                           params, (size_t)li.lds_bytes, st);
 }
 
 }  // namespace dsattn

@@ -154,38 +154,64 @@ def test_copy_probe_copies():
 
 # ---------------------------------------------------------------- bf16 MFMA streaming kernel
 
-def run_mfma_case(clip_len, n_clips, w, P, h, D, g, gen="correlated", scale=0.0, clips_per_task=None,
-                  seed=41, out_dtypes=("f32", "bf16"), what=""):
-    import os
+class planner_env:
+    """Pins planner choices (clips per chunk, wavefronts per workgroup) for one case."""
+
+    def __init__(self, clips_per_task=None, waves_per_block=None):
+        self.vals = {"DSATTN_CLIPS_PER_TASK": clips_per_task,
+                     "DSATTN_WAVES_PER_BLOCK": waves_per_block}
+
+    def __enter__(self):
+        import os
+        self.old = {k: os.environ.get(k) for k in self.vals}
+        for k, v in self.vals.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = str(v)
+
+    def __exit__(self, *exc):
+        import os
+        for k, v in self.old.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
+
+
+def run_mfma_case(n_clips, w, P, h, D, g, gen="correlated", scale=0.0, clips_per_task=None,
+                  waves_per_block=None, seed=41, out_dtypes=("f32", "bf16"), what=""):
+    clip_len = 16
     F = clip_len * n_clips
     q, k, v = make(F, P, h * D, seed, gen, "bf16")
     ref = U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g, scale=scale)
-    old = os.environ.get("DSATTN_CLIPS_PER_TASK")
-    try:
-        if clips_per_task is not None:
-            os.environ["DSATTN_CLIPS_PER_TASK"] = str(clips_per_task)
+    with planner_env(clips_per_task, waves_per_block):
         for od in out_dtypes:
             announce(f"mfma {what} N={n_clips} w={w} P={P} h={h} D={D} G={len(g)} {gen} "
-                     f"scale={scale} M={clips_per_task} out={od}")
+                     f"scale={scale} M={clips_per_task} wpb={waves_per_block} out={od}")
             o, info = U.library_forward(q, k, v, clip_len, n_clips, w, h, g, out_dtype=od,
                                         scale=scale)
             assert info["kernel"] == 1, f"planner did not pick the MFMA kernel: {info}"
             if clips_per_task is not None:
                 assert info["clips_per_task"] == min(clips_per_task, n_clips)
+            if waves_per_block is not None:
+                assert info["block_threads"] == 64 * waves_per_block
             U.assert_parity(o, ref, od, what=what)
-    finally:
-        if old is None:
-            os.environ.pop("DSATTN_CLIPS_PER_TASK", None)
-        else:
-            os.environ["DSATTN_CLIPS_PER_TASK"] = old
+    return info
 
 
 @pytest.mark.parametrize("m", [None, 1, 2, 4, 6])
 def test_mfma_d160_chunking(m):
     # the headline level's shape on a short video: 6 clips, interior and both edge clips,
     # every way of cutting the clips into per-wavefront chunks
-    run_mfma_case(16, 6, 2, 5, 8, 160, synth.stride_global_idx(96, 16), clips_per_task=m,
+    run_mfma_case(6, 2, 5, 8, 160, synth.stride_global_idx(96, 16), clips_per_task=m,
                   what="d160 chunking")
+
+
+@pytest.mark.parametrize("wpb", [1, 2, 4, 8])
+def test_mfma_d160_waves_per_block(wpb):
+    run_mfma_case(5, 2, 3, 8, 160, synth.stride_global_idx(80, 16), clips_per_task=2,
+                  waves_per_block=wpb, what="d160 wpb")
 
 
 @pytest.mark.parametrize("w,g", [
@@ -194,20 +220,47 @@ def test_mfma_d160_chunking(m):
     (8, list(range(0, 48, 3))),             # the paper's own setting: 8 + 8 neighbours, 16 global
     (5, [7, 7, 7, 30, 30, 1]),              # duplicates count twice
     (3, list(range(16))),                   # global set inside clip 0 (all duplicates of local)
+    (0, [5, 40]),                           # no local context beyond the clip itself
+    (0, []),                                # plain per-clip attention
+    (12, [1]),                              # window of 40 frames: three local key tiles
+    (16, list(range(0, 48, 4))),            # w = clip length
 ])
 def test_mfma_d160_context_shapes(w, g):
-    run_mfma_case(16, 3, w, 3, 2, 160, g, gen="iid", clips_per_task=2, what=f"ctx w={w}")
+    run_mfma_case(3, w, 3, 2, 160, g, gen="iid", clips_per_task=2, what=f"ctx w={w}")
+
+
+def test_mfma_reduces_to_full_attention():
+    # no global set and a window covering the whole video: every clip sees all frames
+    info = run_mfma_case(2, 16, 2, 2, 160, [], gen="iid", what="full attention")
+    assert info["local_tiles"] == 3
 
 
 def test_mfma_d160_single_clip_and_tiny_grid():
-    run_mfma_case(16, 1, 2, 1, 1, 160, [3, 9], gen="iid", what="single clip")
-    run_mfma_case(16, 2, 4, 1, 1, 160, [31], gen="iid", clips_per_task=1, what="two clips")
+    run_mfma_case(1, 2, 1, 1, 160, [3, 9], gen="iid", what="single clip")
+    run_mfma_case(2, 4, 1, 1, 160, [31], gen="iid", clips_per_task=1, what="two clips")
 
 
 def test_mfma_d160_peaked_softmax():
     # iid inputs with a 4x larger scale: near one-hot weights, large logits
-    run_mfma_case(16, 4, 2, 3, 2, 160, synth.stride_global_idx(64, 16), gen="iid",
+    run_mfma_case(4, 2, 3, 2, 160, synth.stride_global_idx(64, 16), gen="iid",
                   scale=4.0 / np.sqrt(160.0), what="peaked")
+
+
+@pytest.mark.parametrize("D,h,P", [(80, 8, 5), (80, 2, 3), (40, 8, 7), (40, 4, 2)])
+@pytest.mark.parametrize("w,G", [(2, 16), (0, 0), (8, 5), (12, 16)])
+def test_mfma_other_head_dims(D, h, P, w, G):
+    # head_dim 80 runs two heads per wavefront, head_dim 40 four: padded contraction blocks
+    g = synth.stride_global_idx(64, G) if G else []
+    info = run_mfma_case(4, w, P, h, D, g, gen="iid", clips_per_task=3, what=f"D={D}")
+    assert info["heads_per_wave"] == 160 // D
+
+
+def test_mfma_odd_row_group_count():
+    # 3 positions x 2 heads = 6 row groups: workgroups of 2 wavefronts, not 8
+    info = run_mfma_case(3, 2, 3, 2, 160, [0, 9], what="odd rows")
+    assert info["block_threads"] == 128
+    info = run_mfma_case(3, 2, 5, 1, 160, [0, 9], what="prime rows")
+    assert info["block_threads"] == 64
 
 
 def test_mfma_matches_generic_kernel_on_device():
@@ -220,3 +273,29 @@ def test_mfma_matches_generic_kernel_on_device():
                                flags=B.DSATTN_FLAG_FORCE_GENERIC)
     assert i1["kernel"] == 1 and i2["kernel"] == 0
     assert (o1 - o2).abs().max().item() < 5e-3
+
+
+def test_mfma_is_deterministic():
+    clip_len, n_clips, w, P, h, D = 16, 4, 2, 6, 8, 160
+    g = synth.stride_global_idx(64, 16)
+    q, k, v = make(64, P, h * D, 9, "correlated", "bf16")
+    o1, _ = U.library_forward(q, k, v, clip_len, n_clips, w, h, g)
+    o2, _ = U.library_forward(q, k, v, clip_len, n_clips, w, h, g)
+    assert torch.equal(o1, o2)
+
+
+def test_mfma_locality_and_permutation_on_device():
+    # frames outside a clip's list cannot change its output (bit for bit); permuting the
+    # global set changes nothing beyond rounding order
+    clip_len, n_clips, w, P, h, D = 16, 4, 2, 3, 2, 160
+    g = [0, 40, 63, 17]
+    q, k, v = make(64, P, h * D, 13, "iid", "bf16")
+    base, _ = U.library_forward(q, k, v, clip_len, n_clips, w, h, g, out_dtype="f32")
+    k2, v2 = k.clone(), v.clone()
+    k2[30] += 3.0   # frame 30 belongs to clip 1 and (w = 2) to clip 2's c_pre: not to clips 0, 3
+    v2[30] -= 3.0
+    o, _ = U.library_forward(q, k2, v2, clip_len, n_clips, w, h, g, out_dtype="f32")
+    assert torch.equal(o[:16], base[:16]) and torch.equal(o[48:], base[48:])
+    assert (o[16:48] - base[16:48]).abs().max().item() > 1e-3
+    operm, _ = U.library_forward(q, k, v, clip_len, n_clips, w, h, [17, 63, 0, 40], out_dtype="f32")
+    assert (operm - base).abs().max().item() < 2e-3
