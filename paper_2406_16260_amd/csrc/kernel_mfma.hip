@@ -41,7 +41,9 @@ bool mfma_plan(dsattn_plan_t &pl)
     if (d.io_dtype != DSATTN_BF16 || d.clip_len != 16) return false;
     if (pl.C % 8 != 0) return false;
     const int G = (int)pl.global_idx.size();
-    const int NGT = (G + 15) / 16;
+    // global key tiles: variants exist for 0, 1 and 4 tiles; a partly used tile is masked
+    if (G > 64) return false;
+    const int NGT = G == 0 ? 0 : (G <= 16 ? 1 : 4);
     const int R = 16 + 2 * d.local_ctx;
     const int NLT = (R + 15) / 16;
     const bool out_f32 = d.out_dtype == DSATTN_F32;

@@ -8,6 +8,8 @@ static const MfmaVariant kVariantsD160[] = {
     DSATTN_MFMA_VARIANT(160, 1, 1, 0, 2), DSATTN_MFMA_VARIANT(160, 1, 1, 1, 2),
     DSATTN_MFMA_VARIANT(160, 1, 2, 0, 2), DSATTN_MFMA_VARIANT(160, 1, 2, 1, 2),
     DSATTN_MFMA_VARIANT(160, 1, 3, 0, 2), DSATTN_MFMA_VARIANT(160, 1, 3, 1, 2),
+    // up to 64 global frames: four global key tiles held in registers, one wavefront per SIMD
+    DSATTN_MFMA_VARIANT(160, 1, 1, 4, 1), DSATTN_MFMA_VARIANT(160, 1, 2, 4, 1),
 };
 
 const MfmaVariant *mfma_variants_d160(int *n)

@@ -67,9 +67,10 @@ __device__ __forceinline__ void wave_sync()
     __builtin_amdgcn_wave_barrier();
 }
 
-// WPE = wavefronts per SIMD the register budget is sized for (2: 256 VGPRs, 1: 512).
+// WPE = wavefronts per SIMD the register budget is sized for (2: 256 VGPRs, 1: 512); a
+// workgroup is at most 4 * WPE wavefronts so that it fits one compute unit.
 template <int D, int HPW, int NLT, int NGT, int WPE, bool OUT_F32>
-__global__ __launch_bounds__(512, WPE) void dsattn_mfma_kernel(const MfmaArgs a)
+__global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaArgs a)
 {
     constexpr int SEG = D * HPW;          // bf16 per frame row of this row group
     constexpr int NCH = SEG / 8;          // 16-byte chunks per row

@@ -255,6 +255,15 @@ def test_mfma_other_head_dims(D, h, P, w, G):
     assert info["heads_per_wave"] == 160 // D
 
 
+@pytest.mark.parametrize("D,h,P", [(160, 8, 3), (80, 8, 3), (40, 8, 3), (160, 1, 2)])
+@pytest.mark.parametrize("w,G", [(4, 64), (2, 33), (0, 17), (8, 48)])
+def test_mfma_many_global_frames(D, h, P, w, G):
+    # 17..64 global frames: four global key tiles in registers, one wavefront per SIMD
+    g = synth.random_sorted_global_idx(80, G, seed=3)
+    info = run_mfma_case(5, w, P, h, D, g, gen="iid", clips_per_task=2, what=f"G={G} D={D}")
+    assert info["global_tiles"] == 4 and info["block_threads"] <= 256
+
+
 def test_mfma_odd_row_group_count():
     # 3 positions x 2 heads = 6 row groups: workgroups of 2 wavefronts, not 8
     info = run_mfma_case(3, 2, 3, 2, 160, [0, 9], what="odd rows")
