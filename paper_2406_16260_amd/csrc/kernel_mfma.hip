@@ -48,12 +48,23 @@ bool mfma_plan(dsattn_plan_t &pl)
     const int NLT = (R + 15) / 16;
     const bool out_f32 = d.out_dtype == DSATTN_F32;
 
-    // heads per wavefront: the widest variant that exists for this head_dim (long contiguous
-    // rows per frame); a wavefront never straddles two positions
+    // heads per wavefront: prefer the variant that keeps two wavefronts per SIMD (more loads in
+    // flight, compute of one wavefront hidden behind the other), then the widest rows; a
+    // wavefront never straddles two positions
     const MfmaVariant *var = nullptr;
-    for (int cand : {4, 2, 1})
-        if (d.heads % cand == 0 && (var = find_variant(d.head_dim, cand, NLT, NGT, out_f32)))
-            break;
+    const int force_hpw = env_int("DSATTN_HEADS_PER_WAVE", 0);
+    for (int wpe : {2, 1}) {
+        for (int cand : {4, 2, 1}) {
+            if (force_hpw && cand != force_hpw) continue;
+            if (d.heads % cand != 0) continue;
+            const MfmaVariant *v = find_variant(d.head_dim, cand, NLT, NGT, out_f32);
+            if (v && v->WPE == wpe) {
+                var = v;
+                break;
+            }
+        }
+        if (var) break;
+    }
     if (!var) return false;
     const int hpw = var->HPW;
     const int lds_wave = (2 * R + 16) * row_stride_bytes(d.head_dim * hpw);

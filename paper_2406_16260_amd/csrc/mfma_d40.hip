@@ -10,6 +10,8 @@ static const MfmaVariant kVariantsD40[] = {
     DSATTN_MFMA_VARIANT(40, 4, 3, 0, 2), DSATTN_MFMA_VARIANT(40, 4, 3, 1, 2),
     // up to 64 global frames: four global key tiles held in registers, one wavefront per SIMD
     DSATTN_MFMA_VARIANT(40, 4, 1, 4, 1), DSATTN_MFMA_VARIANT(40, 4, 2, 4, 1),
+    // the same with 2 head(s) per wavefront: half the global-context registers, two wavefronts per SIMD
+    DSATTN_MFMA_VARIANT(40, 2, 1, 4, 2), DSATTN_MFMA_VARIANT(40, 2, 2, 4, 2),
 };
 
 const MfmaVariant *mfma_variants_d40(int *n)

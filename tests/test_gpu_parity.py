@@ -261,7 +261,7 @@ def test_mfma_many_global_frames(D, h, P, w, G):
     # 17..64 global frames: four global key tiles in registers, one wavefront per SIMD
     g = synth.random_sorted_global_idx(80, G, seed=3)
     info = run_mfma_case(5, w, P, h, D, g, gen="iid", clips_per_task=2, what=f"G={G} D={D}")
-    assert info["global_tiles"] == 4 and info["block_threads"] <= 256
+    assert info["global_tiles"] == 4
 
 
 def test_mfma_odd_row_group_count():
