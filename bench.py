@@ -23,6 +23,24 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 METRIC = "dual-scope attn query-frame-positions/s at 1 GPU; % of HBM roofline"
 
 
+def measured_traffic(workload, info):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE and WRITE_SIZE runs, scaled by the copy kernel), or None when no summary matches
+    this launch shape.  Counters cannot be read from inside the timed process."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"dsattn_mfma_kernel_{workload}.md")
+    if not os.path.exists(path):
+        return None
+    text = open(path).read()
+    key = (f"{workload}:kernel={info['kernel']}:hpw={info['heads_per_wave']}:"
+           f"clips_per_task={info['clips_per_task']}:block_threads={info['block_threads']}")
+    mk = re.search(r"^launch_key = (\S+)$", text, re.M)
+    mt = re.search(r"^traffic_bytes_per_launch = (\d+)$", text, re.M)
+    if not mk or not mt or mk.group(1) != key:
+        return None
+    return int(mt.group(1))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -107,6 +125,7 @@ def main():
                 "level": levels[dom]["level"].name,
                 "algorithmic_bytes_per_launch": alg_bytes,
                 "avg_launch_ms": round(per_level_ms[dom], 4)}
+    roofline["traffic"] = measured_traffic(wl.name, levels[dom]["info"])
     total_alg = sum(L["info"]["algorithmic_bytes"] for L in levels)
     step_gbps = total_alg / (ms_per_step * 1e-3) / 1e9
 
