@@ -8,9 +8,8 @@ static const MfmaVariant kVariantsD40[] = {
     DSATTN_MFMA_VARIANT(40, 4, 1, 0, 2), DSATTN_MFMA_VARIANT(40, 4, 1, 1, 2),
     DSATTN_MFMA_VARIANT(40, 4, 2, 0, 2), DSATTN_MFMA_VARIANT(40, 4, 2, 1, 2),
     DSATTN_MFMA_VARIANT(40, 4, 3, 0, 2), DSATTN_MFMA_VARIANT(40, 4, 3, 1, 2),
-    // up to 64 global frames: four global key tiles held in registers, one wavefront per SIMD
-    DSATTN_MFMA_VARIANT(40, 4, 1, 4, 1), DSATTN_MFMA_VARIANT(40, 4, 2, 4, 1),
-    // the same with 2 head(s) per wavefront: half the global-context registers, two wavefronts per SIMD
+    // up to 64 global frames: four global key tiles held in registers; 2 head(s) per wavefront
+    // keep the global context small enough for two wavefronts per SIMD
     DSATTN_MFMA_VARIANT(40, 2, 1, 4, 2), DSATTN_MFMA_VARIANT(40, 2, 2, 4, 2),
 };
 

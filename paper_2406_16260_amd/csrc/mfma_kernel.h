@@ -189,59 +189,87 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
         return __builtin_bit_cast(s16x4, b);
     };
 
-    // ---- global context: registers, MFMA operand form
+    // ---- prologue.  Independent loads are issued together so that the chunk starts after
+    // two memory round trips: (1) global frame indices, boundary frames, Q of the first clip;
+    // (2) global K/V rows, K/V of the first clip.
     bf16x8 kg[NGT > 0 ? NGT : 1][HPW][NKB];
     s16x4 vgt[NGT > 0 ? NGT : 1][HPW][NDT];
     uint4 stQ[NLD], stK[NLD], stV[NLD];
-#pragma unroll
-    for (int tg = 0; tg < NGT; ++tg) {
+    uint4 gK[NLD], gV[NLD];
+
+    // global K/V rows of key tile tg -> gK, gV (zeros past the G-th global frame)
+    auto load_global_tile = [&](int tg) __attribute__((always_inline)) {
+        int gf[NLD];
 #pragma unroll
         for (int r = 0; r < NLD; ++r) {
             const int j = 16 * tg + fq[r];
-            stK[r] = make_uint4(0, 0, 0, 0);
-            stV[r] = make_uint4(0, 0, 0, 0);
-            if (in_tile(r) && j < a.G) {
-                const int64_t goff = (int64_t)a.gidx[j] * FSB + coff[r];
-                stK[r] = *(const uint4 *)(Kb + goff);
-                stV[r] = *(const uint4 *)(Vb + goff);
+            gf[r] = -1;
+            if (in_tile(r) && j < a.G) gf[r] = a.gidx[j];
+        }
+#pragma unroll
+        for (int r = 0; r < NLD; ++r) {
+            gK[r] = make_uint4(0, 0, 0, 0);
+            gV[r] = make_uint4(0, 0, 0, 0);
+            if (gf[r] >= 0) {
+                const int64_t goff = (int64_t)gf[r] * FSB + coff[r];
+                gK[r] = *(const uint4 *)(Kb + goff);
+                gV[r] = *(const uint4 *)(Vb + goff);
             }
         }
-        wave_sync();
-        store_rows(kring, 0, 16, 16, stK);
-        store_rows(vring, 0, 16, 16, stV);
-        wave_sync();
-#pragma unroll
-        for (int hh = 0; hh < HPW; ++hh) {
-#pragma unroll
-            for (int kb = 0; kb < NKB; ++kb) {
-                kg[tg][hh][kb] = read_op32(kring, l16, hh, kb);
-                const bf16x8 av = read_op32(vring, l16, hh, kb);
-#pragma unroll
-                for (int hf = 0; hf < 2; ++hf)
-                    if (2 * kb + hf < NDT) vgt[tg][hh][2 * kb + hf] = vt_from(av, hf);
-            }
-        }
-    }
-    wave_sync();
+    };
 
-    // ---- prime the ring with the 2w frames that precede the first bulk tile
+    // boundary frames that precede the first bulk tile: 2w rows, 16 per local tile
+    if constexpr (NLT >= 2) {
+        load_rows(Kb, 16 * c0 - w, min(16, 2 * w), stK);
+        load_rows(Vb, 16 * c0 - w, min(16, 2 * w), stV);
+    }
+    load_rows(Qb, 16 * c0, 16, stQ);
+    if constexpr (NGT > 0) load_global_tile(0);
+    if constexpr (NLT >= 2) {
+        const int s0 = (16 * c0) % R;  // slot of frame f is (f + w) mod R
+        store_rows(kring, s0, min(16, 2 * w), R, stK);
+        store_rows(vring, s0, min(16, 2 * w), R, stV);
+    }
 #pragma unroll
-    for (int tl = 0; tl + 1 < NLT; ++tl) {
+    for (int tl = 1; tl + 1 < NLT; ++tl) {
         const int nrows = min(16, 2 * w - 16 * tl);
         if (nrows > 0) {
             const int f0 = 16 * c0 - w + 16 * tl;
             load_rows(Kb, f0, nrows, stK);
             load_rows(Vb, f0, nrows, stV);
-            const int s0 = (16 * c0 + 16 * tl) % R;  // slot of frame f is (f + w) mod R
+            const int s0 = (16 * c0 + 16 * tl) % R;
             store_rows(kring, s0, nrows, R, stK);
             store_rows(vring, s0, nrows, R, stV);
         }
     }
-
-    // first bulk tile: Q frames [16 c0, +16), K/V frames [16 c0 + w, +16)
-    load_rows(Qb, 16 * c0, 16, stQ);
+    // first bulk tile of K/V: frames [16 c0 + w, +16)
     load_rows(Kb, 16 * c0 + w, 16, stK);
     load_rows(Vb, 16 * c0 + w, 16, stV);
+
+    // global context into registers in MFMA operand form, staged through the Q/O buffer
+#pragma unroll
+    for (int tg = 0; tg < NGT; ++tg) {
+        if (tg > 0) load_global_tile(tg);
+        wave_sync();
+        store_rows(qo, 0, 16, 16, gK);
+        wave_sync();
+#pragma unroll
+        for (int hh = 0; hh < HPW; ++hh)
+#pragma unroll
+            for (int kb = 0; kb < NKB; ++kb) kg[tg][hh][kb] = read_op32(qo, l16, hh, kb);
+        wave_sync();
+        store_rows(qo, 0, 16, 16, gV);
+        wave_sync();
+#pragma unroll
+        for (int hh = 0; hh < HPW; ++hh)
+#pragma unroll
+            for (int kb = 0; kb < NKB; ++kb) {
+                const bf16x8 av = read_op32(qo, l16, hh, kb);
+#pragma unroll
+                for (int hf = 0; hf < 2; ++hf)
+                    if (2 * kb + hf < NDT) vgt[tg][hh][2 * kb + hf] = vt_from(av, hf);
+            }
+    }
 
     int s_bulk = (16 * c0 + 2 * w) % R;  // ring slot of the bulk tile's first row
     int b0 = (16 * c0) % R;              // ring slot of the window's first frame (16 i - w)
