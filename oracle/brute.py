@@ -21,7 +21,8 @@ def key_frames(a, clip_len, n_clips, w, global_idx):
     return local + [int(g) for g in global_idx]
 
 
-def forward(q, k, v, clip_len, n_clips, w, global_idx, scale=None):
+def forward(q, k, v, clip_len, n_clips, w, global_idx, scale=None, bias_local=0.0,
+            bias_global=0.0):
     """q, k, v: nested lists / arrays indexed [f][p][g][d]. Returns nested lists."""
     F = clip_len * n_clips
     P = len(q[0])
@@ -32,12 +33,15 @@ def forward(q, k, v, clip_len, n_clips, w, global_idx, scale=None):
     out = [[[[0.0] * D for _ in range(H)] for _ in range(P)] for _ in range(F)]
     for a in range(F):
         frames = key_frames(a, clip_len, n_clips, w, global_idx)
+        n_local = len(frames) - len(global_idx)
+        # scope weights (Section 5.1) as logit biases: local keys first, then global keys
+        bias = [bias_local] * n_local + [bias_global] * len(global_idx)
         for p in range(P):
             for g in range(H):
                 logits = []
-                for f in frames:
+                for f, b in zip(frames, bias):
                     logits.append(scale * sum(float(q[a][p][g][d]) * float(k[f][p][g][d])
-                                              for d in range(D)))
+                                              for d in range(D)) + b)
                 top = max(logits)
                 ex = [math.exp(x - top) for x in logits]
                 tot = sum(ex)

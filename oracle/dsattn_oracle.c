@@ -27,9 +27,14 @@
  *
  *   Every query frame a of clip i, at every position p and head g, then does
  *   ordinary softmax attention over that list:
- *     s_j = scale * sum_d Q[a][p][g][d] * K[ctx_j][p][g][d]
+ *     s_j = scale * sum_d Q[a][p][g][d] * K[ctx_j][p][g][d] + b_j
  *     A_j = exp(s_j - max_j s_j) / sum_j exp(s_j - max_j s_j)
  *     O[a][p][g][d] = sum_j A_j * V[ctx_j][p][g][d]
+ *   b_j is the scope weight of Section 5.1 ("the weights of frames in G and N are
+ *   dynamically adjusted"), taken as an additive logit bias: bias_local for the
+ *   keys of the local part, bias_global for the keys of the global part; both 0
+ *   unless the caller sets them (raising a scope's logits by b multiplies its
+ *   unnormalised softmax weights by e^b).
  *   No mask, no positional term.  Outputs of the clips are concatenated along
  *   frames (Section 4.1, v_out = Concat), i.e. O has the layout of Q.
  *
@@ -105,7 +110,7 @@ int oracle_ctx_indices(int64_t clip_len, int64_t n_clips, int64_t w,
 
 /*
  * Forward pass.  Q, K, V, O: [F][P][h][D] doubles, contiguous.
- * scale <= 0 selects 1/sqrt(D).
+ * scale <= 0 selects 1/sqrt(D).  bias_local / bias_global: scope logit biases.
  * weights: NULL, or [F][P][h][lk_max] receiving the softmax weights A_j
  *          (zero padded past the clip's list length).
  * Returns 0 on success, -1 on bad arguments, -2 on allocation failure.
@@ -115,7 +120,7 @@ int oracle_ctx_indices(int64_t clip_len, int64_t n_clips, int64_t w,
 int oracle_forward(int64_t clip_len, int64_t n_clips, int64_t w,
                    int64_t P, int64_t h, int64_t D,
                    const int32_t *global_idx, int64_t n_global, double scale,
-                   const double *Q, const double *K, const double *V,
+                   double bias_local, double bias_global, const double *Q, const double *K, const double *V,
                    double *O, double *weights)
 {
     if (clip_len < 1 || n_clips < 1 || w < 0 || P < 1 || h < 1 || D < 1 || n_global < 0)
@@ -157,7 +162,7 @@ int oracle_forward(int64_t clip_len, int64_t n_clips, int64_t w,
                             const double *k = K + (int64_t)ctx[j] * frame_stride + p * C + g * D;
                             double dot = 0.0;
                             for (int64_t d = 0; d < D; ++d) dot += q[d] * k[d];
-                            s[j] = scale * dot;
+                            s[j] = scale * dot + (j < L - n_global ? bias_local : bias_global);
                             if (s[j] > m) m = s[j];
                         }
                         /* softmax */

@@ -265,6 +265,51 @@ def test_duplicate_frame_counts_twice():
     assert np.abs(o_dup[4:6] - o_nodup[4:6]).max() > 1e-6
 
 
+# ---------------------------------------------------------------- scope weights (Section 5.1)
+
+def test_scope_bias_pins():
+    clip_len, n_clips, w = 4, 3, 1
+    g = [0, 7, 10]
+    q, k, v = rand_qkv(12, 2, 2, 5, seed=31)
+    base = oracle.forward(q, k, v, clip_len, n_clips, w, g, scale=0.7)
+    # equal biases on both scopes cancel in the softmax
+    same = oracle.forward(q, k, v, clip_len, n_clips, w, g, scale=0.7, bias_local=3.5,
+                          bias_global=3.5)
+    np.testing.assert_allclose(same, base, rtol=0, atol=1e-12)
+    # only the difference matters
+    a = oracle.forward(q, k, v, clip_len, n_clips, w, g, scale=0.7, bias_local=1.0, bias_global=3.0)
+    b = oracle.forward(q, k, v, clip_len, n_clips, w, g, scale=0.7, bias_local=0.0, bias_global=2.0)
+    np.testing.assert_allclose(a, b, rtol=0, atol=1e-12)
+    assert np.abs(a - base).max() > 1e-3
+    # a global bias of ln 2 equals listing every global frame twice (weights count twice)
+    dbl = oracle.forward(q, k, v, clip_len, n_clips, w, g + g, scale=0.7)
+    ln2 = oracle.forward(q, k, v, clip_len, n_clips, w, g, scale=0.7, bias_global=math.log(2.0))
+    np.testing.assert_allclose(ln2, dbl, rtol=0, atol=1e-12)
+    # a very negative global bias removes the global scope, a very negative local bias leaves
+    # plain attention over the global frames only (library routine)
+    no_g = oracle.forward(q, k, v, clip_len, n_clips, w, g, scale=0.7, bias_global=-800.0)
+    np.testing.assert_allclose(no_g, oracle.forward(q, k, v, clip_len, n_clips, w, [], scale=0.7),
+                               rtol=0, atol=1e-12)
+    only_g = oracle.forward(q, k, v, clip_len, n_clips, w, g, scale=0.7, bias_local=-800.0)
+    for p in range(2):
+        for hd in range(2):
+            ref = sdpa_f64(q[:, p, hd], k[g, p, hd], v[g, p, hd], 0.7)
+            np.testing.assert_allclose(only_g[:, p, hd], ref, rtol=0, atol=1e-12)
+    # hand-computed two-key case: one local key, one global key, bias b on the global one
+    q1 = np.array([1.0, 1.0]).reshape(2, 1, 1, 1)
+    k1 = np.array([0.25, -0.5]).reshape(2, 1, 1, 1)
+    v1 = np.array([2.0, 6.0]).reshape(2, 1, 1, 1)
+    o = oracle.forward(q1, k1, v1, 1, 2, 0, [1], scale=1.0, bias_global=1.5)
+    wl, wg = math.exp(0.25), math.exp(-0.5 + 1.5)
+    assert abs(o[0, 0, 0, 0] - (wl * 2.0 + wg * 6.0) / (wl + wg)) < 1e-14
+    # the brute force agrees
+    bf = np.array(brute.forward(q, k, v, clip_len, n_clips, w, g, scale=0.7, bias_local=-0.3,
+                                bias_global=2.2))
+    np.testing.assert_allclose(
+        oracle.forward(q, k, v, clip_len, n_clips, w, g, scale=0.7, bias_local=-0.3,
+                       bias_global=2.2), bf, rtol=0, atol=1e-13)
+
+
 # ---------------------------------------------------------------- gather by definition
 
 def test_gather_context_is_index_select():
