@@ -64,6 +64,9 @@ typedef struct dsattn_desc {
     int32_t out_dtype;  /* dsattn_dtype of O (F32 input requires F32 output) */
     float scale;        /* softmax scale; <= 0 selects 1/sqrt(D) */
     uint32_t flags;     /* DSATTN_FLAG_* */
+    float bias_local;   /* scope weights (Section 5.1: the weights of the frames of N and of G are */
+    float bias_global;  /* adjusted per timestep), as additive logit biases of the local / global
+                           keys: logit_j = scale * q.k_j + bias; finite; 0 = the plain method */
 } dsattn_desc;
 
 typedef struct dsattn_plan_s dsattn_plan_t; /* opaque; made by dsattn_plan() */

@@ -36,7 +36,7 @@ class DsattnDesc(ctypes.Structure):
         ("clip_len", ctypes.c_int32), ("n_clips", ctypes.c_int32), ("local_ctx", ctypes.c_int32),
         ("spatial", ctypes.c_int32), ("heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
         ("io_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32), ("scale", ctypes.c_float),
-        ("flags", ctypes.c_uint32),
+        ("flags", ctypes.c_uint32), ("bias_local", ctypes.c_float), ("bias_global", ctypes.c_float),
     ]
 
 
@@ -163,12 +163,13 @@ class Plan:
 
 
 def dsattn_plan(clip_len, n_clips, local_ctx, spatial, heads, head_dim, global_idx,
-                io_dtype=DSATTN_BF16, out_dtype=None, scale=0.0, flags=0, device=0) -> Plan:
+                io_dtype=DSATTN_BF16, out_dtype=None, scale=0.0, flags=0, device=0,
+                bias_local=0.0, bias_global=0.0) -> Plan:
     lib = load()
     if out_dtype is None:
         out_dtype = io_dtype
     desc = DsattnDesc(clip_len, n_clips, local_ctx, spatial, heads, head_dim, io_dtype, out_dtype,
-                      float(scale), flags)
+                      float(scale), flags, float(bias_local), float(bias_global))
     g = np.ascontiguousarray(np.asarray(global_idx, dtype=np.int32).reshape(-1))
     handle = ctypes.c_void_p()
     rc = lib.dsattn_plan(ctypes.byref(desc), g.ctypes.data if g.size else None, int(g.size),

@@ -102,6 +102,8 @@ int dsattn_plan(const dsattn_desc *desc, const int32_t *global_idx, int32_t n_gl
         return fail(DSATTN_EINVAL, "dsattn_plan: fp32 input requires fp32 output");
     if (!(d.scale == d.scale) || std::isinf(d.scale))
         return fail(DSATTN_EINVAL, "dsattn_plan: scale is not finite");
+    if (!std::isfinite(d.bias_local) || !std::isfinite(d.bias_global))
+        return fail(DSATTN_EINVAL, "dsattn_plan: scope biases must be finite");
     const int64_t F = (int64_t)d.clip_len * d.n_clips;
     const int64_t C = (int64_t)d.heads * d.head_dim;
     const int64_t lk_bound = (int64_t)d.clip_len + 2 * (int64_t)d.local_ctx + n_global;

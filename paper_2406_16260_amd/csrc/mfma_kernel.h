@@ -44,6 +44,7 @@ struct MfmaArgs {
     int32_t C;
     int64_t FS;   // frame stride in elements = P * C
     float sc;     // scale * log2(e)
+    float gbias;  // (bias_global - bias_local) * log2(e): the softmax only sees the difference
 };
 
 struct MfmaVariant {
@@ -336,7 +337,8 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
             for (int tg = 0; tg < NGT; ++tg)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float x = (16 * tg + 4 * lg + e < a.G) ? s[tg][e] * a.sc : -INFINITY;
+                    const float x =
+                        (16 * tg + 4 * lg + e < a.G) ? fmaf(s[tg][e], a.sc, a.gbias) : -INFINITY;
                     s[tg][e] = x;
                     mx = fmaxf(mx, x);
                 }

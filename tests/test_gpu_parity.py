@@ -308,3 +308,36 @@ def test_mfma_locality_and_permutation_on_device():
     assert (o[16:48] - base[16:48]).abs().max().item() > 1e-3
     operm, _ = U.library_forward(q, k, v, clip_len, n_clips, w, h, [17, 63, 0, 40], out_dtype="f32")
     assert (operm - base).abs().max().item() < 2e-3
+
+
+# ---------------------------------------------------------------- scope weights (Section 5.1)
+
+@pytest.mark.parametrize("bl,bg", [(0.0, 2.302585), (2.302585, 0.0), (1.5, 1.5), (-3.0, 4.0)])
+def test_scope_biases_both_kernels(bl, bg):
+    # the weight of the global or of the local scope raised, e.g. by ln 10 (a tenfold weight)
+    clip_len, n_clips, w, P, h, D = 16, 4, 2, 3, 2, 160
+    g = synth.stride_global_idx(64, 16)
+    q, k, v = make(64, P, h * D, 23, "iid", "bf16")
+    ref = U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g, bias_local=bl, bias_global=bg)
+    plain = U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g)
+    if bl != bg:
+        assert np.abs(ref - plain).max() > 1e-2   # the biases matter on these inputs
+    for flags, kernel in ((0, 1), (B.DSATTN_FLAG_FORCE_GENERIC, 0)):
+        announce(f"scope bias local={bl} global={bg} kernel={kernel}")
+        o, info = U.library_forward(q, k, v, clip_len, n_clips, w, h, g, out_dtype="f32",
+                                    flags=flags, bias_local=bl, bias_global=bg)
+        assert info["kernel"] == kernel
+        U.assert_parity(o, ref, "f32", what=f"bias {bl},{bg} kernel {kernel}")
+
+
+def test_scope_biases_fp32_and_many_globals():
+    q, k, v = make(12, 5, 2 * 5, 3, "iid", "f32")
+    ref = U.oracle_forward(q, k, v, 4, 3, 1, 2, [0, 7, 10], bias_local=0.4, bias_global=-1.1)
+    o, _ = U.library_forward(q, k, v, 4, 3, 1, 2, [0, 7, 10], bias_local=0.4, bias_global=-1.1)
+    U.assert_parity(o, ref, "f32_strict", what="bias fp32")
+    g = synth.random_sorted_global_idx(80, 40, seed=5)
+    q, k, v = make(80, 2, 8 * 40, 7, "iid", "bf16")
+    ref = U.oracle_forward(q, k, v, 16, 5, 4, 8, g, bias_global=2.302585)
+    o, info = U.library_forward(q, k, v, 16, 5, 4, 8, g, out_dtype="f32", bias_global=2.302585)
+    assert info["kernel"] == 1 and info["global_tiles"] == 4
+    U.assert_parity(o, ref, "f32", what="bias G=40 D=40")
