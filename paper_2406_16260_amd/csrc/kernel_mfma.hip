@@ -150,7 +150,7 @@ hipError_t launch_mfma(const dsattn_plan_t &pl, const void *Q, const void *K, co
     a.C = pl.C;
     a.FS = (int64_t)d.spatial * pl.C;
     a.sc = pl.scale * 1.4426950408889634f;
-    a.gbias = (d.bias_global - d.bias_local) * 1.4426950408889634f;
+    a.gshift = (d.bias_global - d.bias_local) / pl.scale;
 
     // the grid must be exactly chunks x workgroups-per-chunk, each workgroup wpb whole row groups
     const int NC = (d.n_clips + a.M - 1) / a.M;

@@ -43,8 +43,9 @@ struct MfmaArgs {
     int32_t BPC;  // workgroups per chunk = RG / WPB
     int32_t C;
     int64_t FS;   // frame stride in elements = P * C
-    float sc;     // scale * log2(e)
-    float gbias;  // (bias_global - bias_local) * log2(e): the softmax only sees the difference
+    float sc;     // scale * log2(e), > 0
+    float gshift; // (bias_global - bias_local) / scale: the scope biases as a shift of the raw
+                  // global scores (the softmax only sees the difference of the two biases)
 };
 
 struct MfmaVariant {
@@ -126,8 +127,10 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
         voff[r] = (uint32_t)fq[r] * (uint32_t)FSB + coff[r];
         loff[r] = (uint32_t)(fq[r] * RS) + coff[r];
     }
+    // only the last of the NLD lane-loads can reach past the 16-row tile, and only when the
+    // tile is not a whole number of 64-lane loads
     auto in_tile = [&](int r) __attribute__((always_inline)) -> bool {
-        return kFullTile || lane + 64 * r < 16 * NCH;
+        return kFullTile || r + 1 < NLD || lane + 64 * r < 16 * NCH;
     };
 
     // 16 consecutive frames starting at frame0 (wave-uniform); rows >= nrows and frames
@@ -135,9 +138,18 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
     auto load_rows = [&](const unsigned char *base, int frame0, int nrows, uint4(&st)[NLD])
                          __attribute__((always_inline)) {
         const unsigned char *tb = base + (int64_t)frame0 * FSB;
-        if (kFullTile && nrows == 16 && frame0 >= 0 && frame0 + 16 <= F) {
+        if (nrows == 16 && frame0 >= 0 && frame0 + 16 <= F) {
+            // whole tile inside the video: no per-lane frame checks
 #pragma unroll
-            for (int r = 0; r < NLD; ++r) st[r] = *(const uint4 *)(tb + voff[r]);
+            for (int r = 0; r < NLD; ++r) {
+                if (kFullTile || r + 1 < NLD) {
+                    st[r] = *(const uint4 *)(tb + voff[r]);
+                } else {
+                    uint4 x = make_uint4(0, 0, 0, 0);
+                    if (in_tile(r)) x = *(const uint4 *)(tb + voff[r]);
+                    st[r] = x;
+                }
+            }
         } else {
 #pragma unroll
             for (int r = 0; r < NLD; ++r) {
@@ -149,7 +161,7 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
             }
         }
     };
-    // tile rows to LDS rows (slot0 + fq) mod ring of `buf`
+    // tile rows to LDS rows (slot0 + fq) mod ring of `buf`; rows >= nrows are not written
     auto store_rows = [&](unsigned char *buf, int slot0, int nrows, int ring,
                           const uint4(&st)[NLD]) __attribute__((always_inline)) {
 #pragma unroll
@@ -157,6 +169,15 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
             const int wrap = (slot0 + fq[r] >= ring) ? ring : 0;
             if (in_tile(r) && fq[r] < nrows)
                 *(uint4 *)(buf + (slot0 - wrap) * RS + loff[r]) = st[r];
+        }
+    };
+    // the same for a whole 16-row tile
+    auto store_tile = [&](unsigned char *buf, int slot0, int ring, const uint4(&st)[NLD])
+                          __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = 0; r < NLD; ++r) {
+            const int wrap = (slot0 + fq[r] >= ring) ? ring : 0;
+            if (in_tile(r)) *(uint4 *)(buf + (slot0 - wrap) * RS + loff[r]) = st[r];
         }
     };
 
@@ -178,6 +199,9 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
 #pragma unroll
         for (int e = 0; e < 8; ++e)
             sel[hf][e] = (8 * lg + e == 16 * hf + l16) ? (__bf16)1.0f : (__bf16)0.0f;
+
+    // A operand of the 16x16x16 MFMA that is all ones (row sums of P^T)
+    const s16x4 ones = {0x3F80, 0x3F80, 0x3F80, 0x3F80};
 
     // V^T operand (A of the 16x16x16 MFMA) for channels 16*(2kb+hf) .. +15 from the V operand
     // `av` (16 keys x 32 channels): an exact transpose through the matrix core
@@ -252,14 +276,14 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
     for (int tg = 0; tg < NGT; ++tg) {
         if (tg > 0) load_global_tile(tg);
         wave_sync();
-        store_rows(qo, 0, 16, 16, gK);
+        store_tile(qo, 0, 16, gK);
         wave_sync();
 #pragma unroll
         for (int hh = 0; hh < HPW; ++hh)
 #pragma unroll
             for (int kb = 0; kb < NKB; ++kb) kg[tg][hh][kb] = read_op32(qo, l16, hh, kb);
         wave_sync();
-        store_rows(qo, 0, 16, 16, gV);
+        store_tile(qo, 0, 16, gV);
         wave_sync();
 #pragma unroll
         for (int hh = 0; hh < HPW; ++hh)
@@ -278,9 +302,9 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
     for (int i = c0; i < c1; ++i) {
         if (WPB > 1) __builtin_amdgcn_s_barrier();  // pacing only: no data crosses wavefronts
         wave_sync();
-        store_rows(qo, 0, 16, 16, stQ);
-        store_rows(kring, s_bulk, 16, R, stK);
-        store_rows(vring, s_bulk, 16, R, stV);
+        store_tile(qo, 0, 16, stQ);
+        store_tile(kring, s_bulk, R, stK);
+        store_tile(vring, s_bulk, R, stV);
         if (i + 1 < c1) {
             load_rows(Qb, 16 * (i + 1), 16, stQ);
             load_rows(Kb, 16 * (i + 1) + w, 16, stK);
@@ -331,14 +355,18 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
                 }
             }
 
-            // ---- softmax over keys, per query column (fp32)
+            // ---- softmax over keys, per query column (fp32).  The maximum is taken over raw
+            // scores (scale > 0), weights are exp2(raw * sc - max * sc); masked keys sit at -inf
+            // and come out as exact zeros.  The scope bias enters as a shift of the global scores.
             float mx = -INFINITY;
+            const bool g_full = a.G == 16 * NGT;  // no partly used global key tile
 #pragma unroll
             for (int tg = 0; tg < NGT; ++tg)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float x =
-                        (16 * tg + 4 * lg + e < a.G) ? fmaf(s[tg][e], a.sc, a.gbias) : -INFINITY;
+                    float x = s[tg][e];
+                    if (a.gshift != 0.f) x += a.gshift;
+                    if (!g_full && !(16 * tg + 4 * lg + e < a.G)) x = -INFINITY;
                     s[tg][e] = x;
                     mx = fmaxf(mx, x);
                 }
@@ -346,27 +374,27 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
             for (int tl = 0; tl < NLT; ++tl)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float x = lvalid[tl][e] ? s[NGT + tl][e] * a.sc : -INFINITY;
+                    const float x = lvalid[tl][e] ? s[NGT + tl][e] : -INFINITY;
                     s[NGT + tl][e] = x;
                     mx = fmaxf(mx, x);
                 }
             mx = fmaxf(mx, __shfl_xor(mx, 16));
             mx = fmaxf(mx, __shfl_xor(mx, 32));
-            float lsum = 0.f;
+            const float nm = -mx * a.sc;
             s16x4 pt[NT];
+            // the denominator is the sum of the *rounded* weights, taken on the matrix core:
+            // a row of ones times P^T leaves sum_k P^T[k][a] in every row of column a
+            f32x4 den = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int tt = 0; tt < NT; ++tt) {
                 bf16x4 pb;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    pb[e] = (__bf16)__builtin_amdgcn_exp2f(s[tt][e] - mx);  // RNE to bf16
-                    lsum += (float)pb[e];  // denominator from the rounded weights
-                }
+                for (int e = 0; e < 4; ++e)
+                    pb[e] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[tt][e], a.sc, nm));  // RNE
                 pt[tt] = __builtin_bit_cast(s16x4, pb);
+                den = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ones, pt[tt], den, 0, 0, 0);
             }
-            lsum += __shfl_xor(lsum, 16);
-            lsum += __shfl_xor(lsum, 32);
-            const float inv = 1.0f / lsum;
+            const float inv = 1.0f / den[0];
 
             // ---- O^T = V^T P^T
             f32x4 o[NDT];
