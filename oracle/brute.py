@@ -11,18 +11,21 @@ Section 4.1 (own clip plus c_pre / c_post boundary frames).
 import math
 
 
-def key_frames(a, clip_len, n_clips, w, global_idx):
-    """Frame list seen by a query in frame `a`: local part then global part."""
+def key_frames(a, clip_len, n_clips, w, global_idx, window=-1):
+    """Frame list seen by a query in frame `a`: local part then global part.
+    With window >= 0 only local frames within `window` of `a` are kept (Section 4.2)."""
     F = clip_len * n_clips
     clip = a // clip_len
     first = clip * clip_len - w
     last = clip * clip_len + clip_len - 1 + w
     local = [f for f in range(first, last + 1) if 0 <= f < F]
+    if window >= 0:
+        local = [f for f in local if abs(f - a) <= window]
     return local + [int(g) for g in global_idx]
 
 
 def forward(q, k, v, clip_len, n_clips, w, global_idx, scale=None, bias_local=0.0,
-            bias_global=0.0):
+            bias_global=0.0, window=-1):
     """q, k, v: nested lists / arrays indexed [f][p][g][d]. Returns nested lists."""
     F = clip_len * n_clips
     P = len(q[0])
@@ -32,7 +35,7 @@ def forward(q, k, v, clip_len, n_clips, w, global_idx, scale=None, bias_local=0.
         scale = 1.0 / math.sqrt(D)
     out = [[[[0.0] * D for _ in range(H)] for _ in range(P)] for _ in range(F)]
     for a in range(F):
-        frames = key_frames(a, clip_len, n_clips, w, global_idx)
+        frames = key_frames(a, clip_len, n_clips, w, global_idx, window)
         n_local = len(frames) - len(global_idx)
         # scope weights (Section 5.1) as logit biases: local keys first, then global keys
         bias = [bias_local] * n_local + [bias_global] * len(global_idx)

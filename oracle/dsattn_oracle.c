@@ -35,7 +35,13 @@
  *   keys of the local part, bias_global for the keys of the global part; both 0
  *   unless the caller sets them (raising a scope's logits by b multiplies its
  *   unnormalised softmax weights by e^b).
- *   No mask, no positional term.  Outputs of the clips are concatenated along
+ *   Optional sliding window (Section 4.2 describes the local context as the
+ *   neighbouring frames of the query frame a, "typically achieved through window
+ *   attention"): with window = r >= 0 a LOCAL key frame f is visible to the
+ *   query of frame a only if |f - a| <= r; hidden keys get weight exactly 0.
+ *   Global keys are always visible.  window < 0 switches this off (every query
+ *   of the clip sees the clip's whole local list).
+ *   No other mask, no positional term.  Outputs of the clips are concatenated along
  *   frames (Section 4.1, v_out = Concat), i.e. O has the layout of Q.
  *
  * All arithmetic is IEEE double, in the loop order written.  Inputs are
@@ -111,6 +117,7 @@ int oracle_ctx_indices(int64_t clip_len, int64_t n_clips, int64_t w,
 /*
  * Forward pass.  Q, K, V, O: [F][P][h][D] doubles, contiguous.
  * scale <= 0 selects 1/sqrt(D).  bias_local / bias_global: scope logit biases.
+ * window: sliding-window radius for the local keys, or < 0 for none.
  * weights: NULL, or [F][P][h][lk_max] receiving the softmax weights A_j
  *          (zero padded past the clip's list length).
  * Returns 0 on success, -1 on bad arguments, -2 on allocation failure.
@@ -120,7 +127,8 @@ int oracle_ctx_indices(int64_t clip_len, int64_t n_clips, int64_t w,
 int oracle_forward(int64_t clip_len, int64_t n_clips, int64_t w,
                    int64_t P, int64_t h, int64_t D,
                    const int32_t *global_idx, int64_t n_global, double scale,
-                   double bias_local, double bias_global, const double *Q, const double *K, const double *V,
+                   double bias_local, double bias_global, int64_t window,
+                   const double *Q, const double *K, const double *V,
                    double *O, double *weights)
 {
     if (clip_len < 1 || n_clips < 1 || w < 0 || P < 1 || h < 1 || D < 1 || n_global < 0)
@@ -163,6 +171,11 @@ int oracle_forward(int64_t clip_len, int64_t n_clips, int64_t w,
                             double dot = 0.0;
                             for (int64_t d = 0; d < D; ++d) dot += q[d] * k[d];
                             s[j] = scale * dot + (j < L - n_global ? bias_local : bias_global);
+                            if (window >= 0 && j < L - n_global) {
+                                int64_t dist = (int64_t)ctx[j] - a;
+                                if (dist < 0) dist = -dist;
+                                if (dist > window) s[j] = -INFINITY; /* hidden: exp gives 0 */
+                            }
                             if (s[j] > m) m = s[j];
                         }
                         /* softmax */

@@ -310,6 +310,64 @@ def test_scope_bias_pins():
                        bias_global=2.2), bf, rtol=0, atol=1e-13)
 
 
+# ---------------------------------------------------------------- sliding-window local scope (Section 4.2)
+
+def banded_sdpa_f64(q, k, v, scale, radius):
+    """Library attention over the whole sequence with a band mask |f - a| <= radius."""
+    n = q.shape[0]
+    idx = torch.arange(n)
+    mask = (idx[None, :] - idx[:, None]).abs() <= radius
+    tq, tk, tv = (torch.from_numpy(np.ascontiguousarray(x))[None, None] for x in (q, k, v))
+    return torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask,
+                                                            scale=scale)[0, 0].numpy()
+
+
+def test_sliding_window_pins():
+    F, P, h, D = 24, 2, 2, 5
+    q, k, v = rand_qkv(F, P, h, D, seed=17)
+    scale = 0.6
+    # (1) a window that covers every clip's whole list changes nothing
+    base = oracle.forward(q, k, v, 4, 6, 2, [0, 13], scale=scale)
+    wide = oracle.forward(q, k, v, 4, 6, 2, [0, 13], scale=scale, window=4 + 2)
+    assert np.array_equal(wide, base)
+    # (2) radius 0 and no global frames: the only visible key is the frame itself
+    self_only = oracle.forward(q, k, v, 4, 6, 2, [], scale=scale, window=0)
+    np.testing.assert_allclose(self_only, v, rtol=0, atol=1e-15)
+    # (3) with boundary context at least as wide as the window (w >= r) the result cannot
+    # depend on how the frames are cut into clips, and equals banded attention over the
+    # whole video computed by the library routine
+    r = 3
+    outs = [oracle.forward(q, k, v, clip_len, F // clip_len, w, [], scale=scale, window=r)
+            for clip_len, w in ((4, 3), (8, 3), (24, 0), (2, 5), (6, 4))]
+    for o in outs[1:]:
+        np.testing.assert_allclose(o, outs[0], rtol=0, atol=1e-13)
+    for p in range(P):
+        for hd in range(h):
+            ref = banded_sdpa_f64(q[:, p, hd], k[:, p, hd], v[:, p, hd], scale, r)
+            np.testing.assert_allclose(outs[0][:, p, hd], ref, rtol=0, atol=1e-13)
+    # (4) w < r truncates the window at the clip's local range: differs from the full band
+    trunc = oracle.forward(q, k, v, 4, 6, 1, [], scale=scale, window=r)
+    assert np.abs(trunc - outs[0]).max() > 1e-6
+    # (5) global frames stay visible whatever their distance; the brute force agrees,
+    # also together with scope biases
+    g = [23, 0, 11]
+    o = oracle.forward(q, k, v, 4, 6, 2, g, scale=scale, window=1, bias_global=0.8)
+    bf = np.array(brute.forward(q, k, v, 4, 6, 2, g, scale=scale, window=1, bias_global=0.8))
+    np.testing.assert_allclose(o, bf, rtol=0, atol=1e-13)
+    o_nog = oracle.forward(q, k, v, 4, 6, 2, [], scale=scale, window=1)
+    assert np.abs(o - o_nog).max() > 1e-3
+    # (6) weights of hidden keys are exactly zero and the rest still sums to one
+    _, wts = oracle.forward(q, k, v, 4, 6, 2, g, scale=scale, window=1, return_weights=True)
+    np.testing.assert_allclose(wts.sum(-1), 1.0, rtol=0, atol=1e-12)
+    idx, ln = oracle.ctx_indices(4, 6, 2, g)
+    for a in range(F):
+        i = a // 4
+        nloc = ln[i] - len(g)
+        hidden = np.abs(idx[i, :nloc] - a) > 1
+        assert (wts[a][..., :nloc][..., hidden] == 0).all()
+        assert (wts[a][..., :nloc][..., ~hidden] > 0).all()
+
+
 # ---------------------------------------------------------------- gather by definition
 
 def test_gather_context_is_index_select():
