@@ -50,6 +50,9 @@ typedef enum dsattn_dtype { DSATTN_F32 = 0, DSATTN_BF16 = 1 } dsattn_dtype;
 
 /* dsattn_desc.flags */
 #define DSATTN_FLAG_FORCE_GENERIC 1u /* planner must pick the generic vector-ALU kernel */
+#define DSATTN_FLAG_SLIDING_WINDOW 2u /* local keys are also limited to |frame - query frame| <=
+                                         dsattn_desc.window (Section 4.2: the local context as the
+                                         neighbouring frames of the query frame) */
 
 /* Problem statement, in the paper's terms. */
 typedef struct dsattn_desc {
@@ -67,6 +70,9 @@ typedef struct dsattn_desc {
     float bias_local;   /* scope weights (Section 5.1: the weights of the frames of N and of G are */
     float bias_global;  /* adjusted per timestep), as additive logit biases of the local / global
                            keys: logit_j = scale * q.k_j + bias; finite; 0 = the plain method */
+    int32_t window;     /* with DSATTN_FLAG_SLIDING_WINDOW: radius r >= 0; a local key frame f is
+                           visible to the query of frame a iff |f - a| <= r (global keys always
+                           are); ignored without the flag */
 } dsattn_desc;
 
 typedef struct dsattn_plan_s dsattn_plan_t; /* opaque; made by dsattn_plan() */

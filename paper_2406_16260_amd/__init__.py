@@ -11,7 +11,7 @@ _BINDING_NAMES = (
     "dsattn_plan", "dsattn_plan_destroy", "dsattn_plan_ctx_max", "dsattn_plan_ctx_indices",
     "dsattn_plan_launch_info", "dsattn_gather_context", "dsattn_forward", "dsattn_forward_ctx",
     "dsattn_copy_probe", "dsattn_strerror", "dsattn_last_error", "Plan", "DsattnError",
-    "DSATTN_F32", "DSATTN_BF16", "DSATTN_FLAG_FORCE_GENERIC",
+    "DSATTN_F32", "DSATTN_BF16", "DSATTN_FLAG_FORCE_GENERIC", "DSATTN_FLAG_SLIDING_WINDOW",
 )
 
 

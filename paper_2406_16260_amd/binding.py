@@ -23,6 +23,7 @@ DSATTN_ENODEVICE = -5
 DSATTN_F32 = 0
 DSATTN_BF16 = 1
 DSATTN_FLAG_FORCE_GENERIC = 1
+DSATTN_FLAG_SLIDING_WINDOW = 2
 
 EXPORTS = (
     "dsattn_plan", "dsattn_plan_destroy", "dsattn_plan_ctx_max", "dsattn_plan_ctx_indices",
@@ -37,6 +38,7 @@ class DsattnDesc(ctypes.Structure):
         ("spatial", ctypes.c_int32), ("heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
         ("io_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32), ("scale", ctypes.c_float),
         ("flags", ctypes.c_uint32), ("bias_local", ctypes.c_float), ("bias_global", ctypes.c_float),
+        ("window", ctypes.c_int32),
     ]
 
 
@@ -164,12 +166,14 @@ class Plan:
 
 def dsattn_plan(clip_len, n_clips, local_ctx, spatial, heads, head_dim, global_idx,
                 io_dtype=DSATTN_BF16, out_dtype=None, scale=0.0, flags=0, device=0,
-                bias_local=0.0, bias_global=0.0) -> Plan:
+                bias_local=0.0, bias_global=0.0, window=None) -> Plan:
+    """window: sliding-window radius of the local scope (sets DSATTN_FLAG_SLIDING_WINDOW), or None."""
     lib = load()
     if out_dtype is None:
         out_dtype = io_dtype
     desc = DsattnDesc(clip_len, n_clips, local_ctx, spatial, heads, head_dim, io_dtype, out_dtype,
-                      float(scale), flags, float(bias_local), float(bias_global))
+                      float(scale), flags | (DSATTN_FLAG_SLIDING_WINDOW if window is not None else 0),
+                      float(bias_local), float(bias_global), int(window) if window is not None else 0)
     g = np.ascontiguousarray(np.asarray(global_idx, dtype=np.int32).reshape(-1))
     handle = ctypes.c_void_p()
     rc = lib.dsattn_plan(ctypes.byref(desc), g.ctypes.data if g.size else None, int(g.size),

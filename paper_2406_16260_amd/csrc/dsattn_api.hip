@@ -104,6 +104,8 @@ int dsattn_plan(const dsattn_desc *desc, const int32_t *global_idx, int32_t n_gl
         return fail(DSATTN_EINVAL, "dsattn_plan: scale is not finite");
     if (!std::isfinite(d.bias_local) || !std::isfinite(d.bias_global))
         return fail(DSATTN_EINVAL, "dsattn_plan: scope biases must be finite");
+    if ((d.flags & DSATTN_FLAG_SLIDING_WINDOW) && d.window < 0)
+        return fail(DSATTN_EINVAL, "dsattn_plan: sliding window radius must be >= 0");
     const int64_t F = (int64_t)d.clip_len * d.n_clips;
     const int64_t C = (int64_t)d.heads * d.head_dim;
     const int64_t lk_bound = (int64_t)d.clip_len + 2 * (int64_t)d.local_ctx + n_global;
@@ -124,6 +126,7 @@ int dsattn_plan(const dsattn_desc *desc, const int32_t *global_idx, int32_t n_gl
         pl->C = (int32_t)C;
         pl->device = device;
         pl->scale = d.scale > 0.f ? d.scale : 1.0f / sqrtf((float)d.head_dim);
+        pl->window = (d.flags & DSATTN_FLAG_SLIDING_WINDOW) ? d.window : -1;
         pl->global_idx.assign(global_idx, global_idx + n_global);
         build_ctx_table(*pl);
     } catch (const std::bad_alloc &) {

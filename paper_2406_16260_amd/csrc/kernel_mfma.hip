@@ -144,6 +144,7 @@ hipError_t launch_mfma(const dsattn_plan_t &pl, const void *Q, const void *K, co
     a.w = d.local_ctx;
     a.G = (int32_t)pl.global_idx.size();
     a.R = 16 + 2 * d.local_ctx;
+    a.window = pl.window;
     a.M = li.clips_per_task;
     a.RG = d.spatial * (d.heads / li.heads_per_wave);
     a.BPC = a.RG / wpb;

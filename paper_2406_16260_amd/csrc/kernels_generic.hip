@@ -126,7 +126,7 @@ __global__ __launch_bounds__(64) void generic_attn_kernel(
     const Tin *__restrict__ Q, const Tin *__restrict__ K, const Tin *__restrict__ V,
     Tout *__restrict__ O, const int32_t *__restrict__ ctx_idx, const int32_t *__restrict__ ctx_len,
     int clip_len, int P, int h, int D, int lk_max, float scale, int ctx_mode, int n_global,
-    float bias_local, float bias_global)
+    float bias_local, float bias_global, int window)
 {
     extern __shared__ float smem[];
     float *sp = smem;
@@ -157,7 +157,9 @@ __global__ __launch_bounds__(64) void generic_attn_kernel(
             float dot = 0.f;
             for (int d = 0; d < D; ++d) dot = fmaf(sq[d], to_f32(k[d]), dot);
             // scope weights: keys [0, L - n_global) are local, the rest global
-            const float s = dot * scale + (j < L - n_global ? bias_local : bias_global);
+            float s = dot * scale + (j < L - n_global ? bias_local : bias_global);
+            // sliding window: a local key further than `window` frames from the query is hidden
+            if (window >= 0 && j < L - n_global && abs(ctx[j] - a) > window) s = -INFINITY;
             sp[j] = s;
             m = fmaxf(m, s);
         }
@@ -198,7 +200,8 @@ hipError_t launch_generic(const dsattn_plan_t &pl, const void *Q, const void *K,
     hipLaunchKernelGGL((generic_attn_kernel<TI, TO>), grid, block, lds, st, (const TI *)Q,        \
                        (const TI *)K, (const TI *)V, (TO *)O, pl.d_ctx_idx, pl.d_ctx_len,         \
                        d.clip_len, d.spatial, d.heads, d.head_dim, pl.lk_max, pl.scale,           \
-                       ctx_mode ? 1 : 0, (int)pl.global_idx.size(), d.bias_local, d.bias_global)
+                       ctx_mode ? 1 : 0, (int)pl.global_idx.size(), d.bias_local, d.bias_global,    \
+                       pl.window)
     if (d.io_dtype == DSATTN_F32)
         DSATTN_LAUNCH_GENERIC(float, float);
     else if (d.out_dtype == DSATTN_F32)

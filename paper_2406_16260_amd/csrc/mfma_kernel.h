@@ -38,6 +38,7 @@ struct MfmaArgs {
     void *O;
     const int32_t *gidx;  // device [G]
     int32_t N, F, h, w, G, R;
+    int32_t window;  // sliding-window radius of the local scope, -1 = none
     int32_t M;    // clips per chunk
     int32_t RG;   // row groups = P * h / HPW
     int32_t BPC;  // workgroups per chunk = RG / WPB
@@ -324,11 +325,13 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
             for (int e = 0; e < 4; ++e) {
                 const int s = 16 * tl + 4 * lg + e;
                 bool ok = s < R;
-                if (!interior) {
+                if (!interior || a.window >= 0) {
                     int rel = s - b0;
                     if (rel < 0) rel += R;
                     const int f = 16 * i - w + rel;
                     ok = ok && f >= 0 && f < F;
+                    // sliding window: key frame f against this lane's query frame 16 i + l16
+                    if (a.window >= 0) ok = ok && abs(rel - w - l16) <= a.window;
                 }
                 lvalid[tl][e] = ok;
             }

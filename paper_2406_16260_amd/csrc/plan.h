@@ -14,6 +14,7 @@ struct dsattn_plan_s {
     int32_t C;       // heads * head_dim
     int32_t lk_max;  // longest context list
     float scale;     // resolved softmax scale
+    int32_t window;  // sliding-window radius of the local scope, -1 = none
     int device;      // HIP ordinal or -1
 
     std::vector<int32_t> global_idx;  // host copy, caller order

@@ -22,7 +22,7 @@ def dt_code(name):
 
 
 def library_forward(q, k, v, clip_len, n_clips, w, heads, gidx, out_dtype=None, scale=0.0,
-                    flags=0, bias_local=0.0, bias_global=0.0):
+                    flags=0, bias_local=0.0, bias_global=0.0, window=None):
     """q, k, v: CUDA tensors [F, P, C]. Returns (O tensor on device, launch info dict)."""
     F, P, C = q.shape
     io = "f32" if q.dtype == torch.float32 else "bf16"
@@ -30,7 +30,7 @@ def library_forward(q, k, v, clip_len, n_clips, w, heads, gidx, out_dtype=None, 
     plan = B.dsattn_plan(clip_len, n_clips, w, P, heads, C // heads, gidx, io_dtype=dt_code(io),
                          out_dtype=dt_code(out_dtype), scale=scale, flags=flags,
                          device=q.device.index or 0, bias_local=bias_local,
-                         bias_global=bias_global)
+                         bias_global=bias_global, window=window)
     o = torch.full((F, P, C), float("nan"), dtype=synth.torch_dtype(out_dtype), device=q.device)
     B.dsattn_forward(plan, q, k, v, o)
     torch.cuda.synchronize()
@@ -40,7 +40,7 @@ def library_forward(q, k, v, clip_len, n_clips, w, heads, gidx, out_dtype=None, 
 
 
 def oracle_forward(q, k, v, clip_len, n_clips, w, heads, gidx, scale=0.0, positions=None,
-                   bias_local=0.0, bias_global=0.0):
+                   bias_local=0.0, bias_global=0.0, window=None):
     """Oracle on the exact upcast of the same tensors; optionally on a subset of positions.
     Returns O as [F, P', C] float64."""
     if positions is not None:
@@ -48,7 +48,8 @@ def oracle_forward(q, k, v, clip_len, n_clips, w, heads, gidx, scale=0.0, positi
         q, k, v = (t.index_select(1, idx) for t in (q, k, v))
     qn, kn, vn = (synth.to_f64_numpy(t, heads) for t in (q, k, v))
     o = oracle.forward(qn, kn, vn, clip_len, n_clips, w, gidx, scale=scale,
-                       bias_local=bias_local, bias_global=bias_global)
+                       bias_local=bias_local, bias_global=bias_global,
+                       window=-1 if window is None else window)
     return o.reshape(o.shape[0], o.shape[1], -1)
 
 

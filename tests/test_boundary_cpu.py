@@ -31,7 +31,7 @@ def raw_plan(desc_kwargs, gidx, device=-1):
     lib = B.load()
     d = dict(clip_len=4, n_clips=2, local_ctx=1, spatial=16, heads=1, head_dim=8,
              io_dtype=B.DSATTN_F32, out_dtype=B.DSATTN_F32, scale=0.0, flags=0, bias_local=0.0,
-             bias_global=0.0)
+             bias_global=0.0, window=0)
     d.update(desc_kwargs)
     desc = B.DsattnDesc(**d)
     g = np.asarray(gidx, dtype=np.int32)
@@ -48,6 +48,7 @@ def raw_plan(desc_kwargs, gidx, device=-1):
     (dict(io_dtype=B.DSATTN_F32, out_dtype=B.DSATTN_BF16), [0]),
     (dict(scale=float("nan")), [0]), (dict(scale=float("inf")), [0]),
     (dict(bias_local=float("nan")), [0]), (dict(bias_global=float("-inf")), [0]),
+    (dict(flags=B.DSATTN_FLAG_SLIDING_WINDOW, window=-1), [0]),
     (dict(), [8]), (dict(), [-1]), (dict(), [0, 3, 99]),
 ])
 def test_plan_rejects_bad_arguments(kw, g):

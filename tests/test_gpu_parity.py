@@ -341,3 +341,48 @@ def test_scope_biases_fp32_and_many_globals():
     o, info = U.library_forward(q, k, v, 16, 5, 4, 8, g, out_dtype="f32", bias_global=2.302585)
     assert info["kernel"] == 1 and info["global_tiles"] == 4
     U.assert_parity(o, ref, "f32", what="bias G=40 D=40")
+
+
+# ---------------------------------------------------------------- sliding-window local scope (Section 4.2)
+
+@pytest.mark.parametrize("w,r,G", [(8, 8, 16), (2, 1, 3), (4, 0, 0), (2, 30, 5), (3, 5, 64), (16, 12, 0)])
+def test_sliding_window_both_kernels(w, r, G):
+    clip_len, n_clips, P, h, D = 16, 4, 3, 2, 160
+    g = synth.random_sorted_global_idx(64, G, seed=11).tolist() if G else []
+    q, k, v = make(64, P, h * D, 31, "iid", "bf16")
+    ref = U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g, window=r)
+    if r < 16 + w - 1:
+        plain = U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g)
+        assert np.abs(ref - plain).max() > 1e-2   # the window matters on these inputs
+    for flags, kernel in ((0, 1), (B.DSATTN_FLAG_FORCE_GENERIC, 0)):
+        announce(f"sliding window w={w} r={r} G={G} kernel={kernel}")
+        o, info = U.library_forward(q, k, v, clip_len, n_clips, w, h, g, out_dtype="f32",
+                                    flags=flags, window=r, scale=2.0 / np.sqrt(160.0))
+        ref2 = U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g, window=r,
+                                scale=2.0 / np.sqrt(160.0))
+        assert info["kernel"] == kernel
+        U.assert_parity(o, ref2, "f32", what=f"window w={w} r={r} kernel {kernel}")
+
+
+def test_sliding_window_partition_invariance_on_device():
+    # with w >= r the clip partition cannot matter: 2 clips chunked differently, and the fp32
+    # generic kernel with other clip lengths, all agree with banded attention over the video
+    F, P, h, D, r = 64, 2, 2, 160, 5
+    q, k, v = make(F, P, h * D, 37, "iid", "bf16")
+    ref = U.oracle_forward(q, k, v, F, 1, 0, h, [], window=r)      # one clip = the whole video
+    with planner_env(clips_per_task=1):
+        o1, i1 = U.library_forward(q, k, v, 16, 4, 5, h, [], out_dtype="f32", window=r)
+    with planner_env(clips_per_task=4):
+        o2, i2 = U.library_forward(q, k, v, 16, 4, 8, h, [], out_dtype="f32", window=r)
+    o3, i3 = U.library_forward(q, k, v, 8, 8, 6, h, [], out_dtype="f32", window=r)   # generic
+    assert i1["kernel"] == 1 and i2["kernel"] == 1 and i3["kernel"] == 0
+    for o in (o1, o2, o3):
+        U.assert_parity(o, ref, "f32", what="window partition invariance")
+
+
+def test_sliding_window_fp32_with_biases():
+    q, k, v = make(24, 5, 2 * 6, 3, "iid", "f32")
+    kw = dict(bias_local=0.3, bias_global=-0.7, window=2)
+    ref = U.oracle_forward(q, k, v, 4, 6, 3, 2, [23, 0, 11], **kw)
+    o, _ = U.library_forward(q, k, v, 4, 6, 3, 2, [23, 0, 11], **kw)
+    U.assert_parity(o, ref, "f32_strict", what="window fp32")
