@@ -156,6 +156,7 @@ int dsattn_plan(const dsattn_desc *desc, const int32_t *global_idx, int32_t n_gl
         if (e == hipSuccess && !pl->global_idx.empty())
             e = hipMemcpy(pl->d_global_idx, pl->global_idx.data(),
                           pl->global_idx.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+        if (e == hipSuccess && pl->launch.kernel == 1) e = mfma_prepare(*pl);
         (void)hipSetDevice(prev);
         if (e != hipSuccess) {
             int code = e == hipErrorOutOfMemory ? DSATTN_ENOMEM : DSATTN_EHIP;
@@ -262,6 +263,9 @@ int dsattn_forward(const dsattn_plan_t *plan, const void *Q, const void *K, cons
     const size_t nout = n * dtype_size(plan->desc.out_dtype);
     if (overlaps(O, nout, Q, nin) || overlaps(O, nout, K, nin) || overlaps(O, nout, V, nin))
         return fail(DSATTN_EINVAL, "dsattn_forward: O overlaps an input");
+    if (plan->launch.kernel != 1 && !generic_supported(*plan))
+        return fail(DSATTN_EUNSUPPORTED, "dsattn_forward: context list or problem too large for "
+                                         "the generic kernel");
     DeviceGuard g(plan->device);
     if (g.err != hipSuccess) return hip_fail(g.err, "dsattn_forward: hipSetDevice");
     hipError_t e = plan->launch.kernel == 1
@@ -286,6 +290,9 @@ int dsattn_forward_ctx(const dsattn_plan_t *plan, const void *Q, const void *Kct
     const size_t nout = n * dtype_size(plan->desc.out_dtype);
     if (overlaps(O, nout, Q, nin) || overlaps(O, nout, Kctx, nctx) || overlaps(O, nout, Vctx, nctx))
         return fail(DSATTN_EINVAL, "dsattn_forward_ctx: O overlaps an input");
+    if (!generic_supported(*plan))
+        return fail(DSATTN_EUNSUPPORTED, "dsattn_forward_ctx: context list or problem too large "
+                                         "for the generic kernel");
     DeviceGuard g(plan->device);
     if (g.err != hipSuccess) return hip_fail(g.err, "dsattn_forward_ctx: hipSetDevice");
     hipError_t e = launch_generic(*plan, Q, Kctx, Vctx, O, true, (hipStream_t)stream);

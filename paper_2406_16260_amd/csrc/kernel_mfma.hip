@@ -122,6 +122,20 @@ bool mfma_plan(dsattn_plan_t &pl)
     return true;
 }
 
+// Raises the kernel's dynamic-LDS cap on the current device to the whole 160 KB (the default
+// cap is 64 KB).  Done once per plan, outside the launch path, so that dsattn_forward makes no
+// call other than the launch itself (it can be captured into a HIP graph).  The cap is always
+// the maximum: plans that share a variant must not lower each other's limit.
+hipError_t mfma_prepare(const dsattn_plan_t &pl)
+{
+    const dsattn_desc &d = pl.desc;
+    const dsattn_launch_info &li = pl.launch;
+    const MfmaVariant *v = find_variant(d.head_dim, li.heads_per_wave, li.local_tiles,
+                                        li.global_tiles, d.out_dtype == DSATTN_F32);
+    if (!v) return hipErrorInvalidValue;
+    return hipFuncSetAttribute(v->fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
+}
+
 hipError_t launch_mfma(const dsattn_plan_t &pl, const void *Q, const void *K, const void *V,
                        void *O, hipStream_t st)
 {
@@ -158,11 +172,6 @@ hipError_t launch_mfma(const dsattn_plan_t &pl, const void *Q, const void *K, co
     if (a.RG % wpb != 0 || (int64_t)a.BPC * NC * wpb != (int64_t)li.n_tasks)
         return hipErrorInvalidValue;
 
-    if (li.lds_bytes > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(v->fn, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           li.lds_bytes);
-        if (e != hipSuccess) return e;
-    }
     void *params[] = {&a};
     return hipLaunchKernel(v->fn, dim3((unsigned)(a.BPC * NC)), dim3((unsigned)li.block_threads),
                            params, (size_t)li.lds_bytes, st);

@@ -34,19 +34,19 @@ hipError_t launch_copy(void *dst, const void *src, int64_t bytes, hipStream_t st
     return hipGetLastError();
 }
 
-// One context row (clip i, slot j) per blockIdx.y; blockIdx.x strides over the frame slab.
+// One context row (clip i, slot j) per blockIdx.x; blockIdx.y strides over the frame slab.
 // slab16 = 16-byte units in one frame slab [P, C].
 __global__ __launch_bounds__(256) void gather16_kernel(uint4 *__restrict__ dst,
                                                        const uint4 *__restrict__ src,
                                                        const int32_t *__restrict__ ctx_idx,
                                                        int64_t slab16)
 {
-    const int64_t row = blockIdx.y;
+    const int64_t row = blockIdx.x;
     const int32_t f = ctx_idx[row];
     uint4 *out = dst + row * slab16;
     const uint4 zero = make_uint4(0, 0, 0, 0);
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int64_t i = (int64_t)blockIdx.y * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.y * blockDim.x;
     if (f >= 0) {
         const uint4 *in = src + (int64_t)f * slab16;
         for (; i < slab16; i += stride) out[i] = in[i];
@@ -62,11 +62,11 @@ __global__ __launch_bounds__(256) void gather_elem_kernel(T *__restrict__ dst,
                                                           const int32_t *__restrict__ ctx_idx,
                                                           int64_t slab)
 {
-    const int64_t row = blockIdx.y;
+    const int64_t row = blockIdx.x;
     const int32_t f = ctx_idx[row];
     T *out = dst + row * slab;
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int64_t i = (int64_t)blockIdx.y * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.y * blockDim.x;
     for (; i < slab; i += stride) out[i] = f >= 0 ? src[(int64_t)f * slab + i] : T(0);
 }
 
@@ -74,25 +74,25 @@ hipError_t launch_gather(const dsattn_plan_t &pl, const void *X, void *Xctx, hip
 {
     const int64_t rows = (int64_t)pl.desc.n_clips * pl.lk_max;
     if (rows == 0) return hipSuccess;
-    if (rows > 65535) return hipErrorInvalidValue;
+    if (rows > 0x7fffffffLL) return hipErrorInvalidValue;
     const int64_t esz = pl.desc.io_dtype == DSATTN_BF16 ? 2 : 4;
     const int64_t slab_bytes = (int64_t)pl.desc.spatial * pl.C * esz;
     if (slab_bytes % 16 == 0) {
         const int64_t slab16 = slab_bytes / 16;
         int64_t bx = (slab16 + 256 * 4 - 1) / (256 * 4);
         bx = bx < 1 ? 1 : (bx > 4096 ? 4096 : bx);
-        hipLaunchKernelGGL(gather16_kernel, dim3((unsigned)bx, (unsigned)rows), dim3(256), 0, st,
+        hipLaunchKernelGGL(gather16_kernel, dim3((unsigned)rows, (unsigned)bx), dim3(256), 0, st,
                            (uint4 *)Xctx, (const uint4 *)X, pl.d_ctx_idx, slab16);
     } else {
         const int64_t slab = slab_bytes / esz;
         int64_t bx = (slab + 256 * 4 - 1) / (256 * 4);
         bx = bx < 1 ? 1 : (bx > 4096 ? 4096 : bx);
         if (esz == 2)
-            hipLaunchKernelGGL(gather_elem_kernel<uint16_t>, dim3((unsigned)bx, (unsigned)rows),
+            hipLaunchKernelGGL(gather_elem_kernel<uint16_t>, dim3((unsigned)rows, (unsigned)bx),
                                dim3(256), 0, st, (uint16_t *)Xctx, (const uint16_t *)X,
                                pl.d_ctx_idx, slab);
         else
-            hipLaunchKernelGGL(gather_elem_kernel<uint32_t>, dim3((unsigned)bx, (unsigned)rows),
+            hipLaunchKernelGGL(gather_elem_kernel<uint32_t>, dim3((unsigned)rows, (unsigned)bx),
                                dim3(256), 0, st, (uint32_t *)Xctx, (const uint32_t *)X,
                                pl.d_ctx_idx, slab);
     }
@@ -185,6 +185,16 @@ __global__ __launch_bounds__(64) void generic_attn_kernel(
         }
         __syncthreads();
     }
+}
+
+// The generic kernel keeps one clip's scores and one query row in LDS (64 KB cap) and
+// numbers its wavefront tasks in 31 bits.
+bool generic_supported(const dsattn_plan_t &pl)
+{
+    const dsattn_desc &d = pl.desc;
+    const int64_t tasks = (int64_t)d.n_clips * d.spatial * d.heads;
+    const size_t lds = (size_t)(pl.lk_max + d.head_dim) * sizeof(float);
+    return tasks <= 0x7fffffffLL && lds <= 64 * 1024;
 }
 
 hipError_t launch_generic(const dsattn_plan_t &pl, const void *Q, const void *K, const void *V,

@@ -386,3 +386,101 @@ def test_sliding_window_fp32_with_biases():
     ref = U.oracle_forward(q, k, v, 4, 6, 3, 2, [23, 0, 11], **kw)
     o, _ = U.library_forward(q, k, v, 4, 6, 3, 2, [23, 0, 11], **kw)
     U.assert_parity(o, ref, "f32_strict", what="window fp32")
+
+
+# ---------------------------------------------------------------- streams, graphs, limits
+
+def test_forward_on_side_stream_and_two_plans():
+    clip_len, n_clips, w, P, h, D = 16, 4, 2, 6, 8, 160
+    g = synth.stride_global_idx(64, 16)
+    q, k, v = make(64, P, h * D, 51, "correlated", "bf16")
+    ref = U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g)
+    p1 = B.dsattn_plan(clip_len, n_clips, w, P, h, D, g, device=0)
+    p2 = B.dsattn_plan(clip_len, n_clips, w, P, h, D, g, out_dtype=B.DSATTN_F32, device=0)
+    o1 = torch.empty_like(q)
+    o2 = torch.empty(q.shape, dtype=torch.float32, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        B.dsattn_forward(p1, q, k, v, o1, side)
+    B.dsattn_forward(p2, q, k, v, o2)          # on the current stream, concurrently
+    side.synchronize()
+    torch.cuda.synchronize()
+    U.assert_parity(o1, ref, "bf16", what="side stream")
+    U.assert_parity(o2, ref, "f32", what="current stream")
+    p1.close()
+    p2.close()
+
+
+def test_forward_in_hip_graph_replays():
+    # dsattn_forward is one kernel launch and nothing else: it can be captured and replayed
+    clip_len, n_clips, w, P, h, D = 16, 5, 2, 4, 8, 160
+    g = synth.stride_global_idx(80, 16)
+    q, k, v = make(80, P, h * D, 61, "correlated", "bf16")
+    plan = B.dsattn_plan(clip_len, n_clips, w, P, h, D, g, device=0)
+    eager = torch.empty_like(q)
+    B.dsattn_forward(plan, q, k, v, eager)
+    torch.cuda.synchronize()
+    out = torch.zeros_like(q)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.dsattn_forward(plan, q, k, v, out)
+    for rep in range(4):
+        out.fill_(0)                           # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {rep} differs from the eager result"
+    # new inputs in the same buffers are picked up by the next replay
+    q2, k2, v2 = make(80, P, h * D, 62, "correlated", "bf16")
+    q.copy_(q2)
+    k.copy_(k2)
+    v.copy_(v2)
+    B.dsattn_forward(plan, q, k, v, eager)
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out, eager)
+    plan.close()
+
+
+def test_generic_kernel_limit_is_reported():
+    # a context list too long for the generic kernel's LDS is refused, not launched
+    lib = B.load()
+    F = 20000
+    plan = B.dsattn_plan(1, F, F, 1, 1, 8, [], io_dtype=B.DSATTN_F32, device=0)
+    x = torch.zeros((F, 1, 8), device=DEV)
+    o = torch.zeros_like(x)
+    st = torch.cuda.current_stream().cuda_stream
+    rc = lib.dsattn_forward(plan.handle, x.data_ptr(), x.data_ptr(), x.data_ptr(), o.data_ptr(), st)
+    assert rc == B.DSATTN_EUNSUPPORTED and "generic" in B.dsattn_last_error()
+    plan.close()
+
+
+def test_randomised_shapes_against_oracle():
+    # seeded sweep over shapes the planner sends to either kernel
+    rng = np.random.default_rng(2024)
+    for case in range(24):
+        D = int(rng.choice([40, 80, 160, 24, 64]))
+        h = int(rng.choice([1, 2, 4, 8]))
+        clip_len = 16 if D in (40, 80, 160) and rng.random() < 0.8 else int(rng.integers(1, 20))
+        n_clips = int(rng.integers(1, 7))
+        F = clip_len * n_clips
+        w = int(rng.integers(0, 18))
+        G = int(rng.choice([0, 1, 5, 16, 17, 40, 64]))
+        g = rng.integers(0, F, size=G).tolist()
+        P = int(rng.integers(1, 6))
+        window = None if rng.random() < 0.6 else int(rng.integers(0, 12))
+        bg = 0.0 if rng.random() < 0.6 else float(rng.normal())
+        announce(f"random case {case}: D={D} h={h} Fc={clip_len} N={n_clips} w={w} G={G} P={P} "
+                 f"window={window} bias_global={bg:.3f}")
+        q, k, v = make(F, P, h * D, 1000 + case, "iid", "bf16")
+        ref = U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g, window=window, bias_global=bg)
+        o, info = U.library_forward(q, k, v, clip_len, n_clips, w, h, g, out_dtype="f32",
+                                    window=window, bias_global=bg)
+        # MFMA variants: clip length 16, head_dim 40/80/160, w <= 16 with up to 16 global frames
+        # (160/D heads per wavefront), w <= 8 with 17..64 (80/D heads per wavefront, 1 at D = 160)
+        expect_mfma = clip_len == 16 and D in (40, 80, 160) and \
+            ((w <= 16 and h % (160 // D) == 0) if G <= 16 else
+             (w <= 8 and (D == 160 or h % (80 // D) == 0)))
+        assert info["kernel"] == (1 if expect_mfma else 0), (info, case)
+        U.assert_parity(o, ref, "f32", what=f"random case {case}")
