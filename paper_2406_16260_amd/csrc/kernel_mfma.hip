@@ -71,12 +71,16 @@ bool mfma_plan(dsattn_plan_t &pl)
     if (lds_wave > kLdsPerCu) return false;
     const int RG = d.spatial * (d.heads / hpw);
 
-    // wavefronts per workgroup: as many neighbouring row groups as LDS and the register budget
-    // allow (their rows are contiguous in memory and are fetched together)
+    // wavefronts per workgroup.  The wavefronts of a workgroup fetch neighbouring rows together
+    // (one barrier per clip), so a workgroup should span at least one whole position (all its
+    // heads: a contiguous, line-aligned run per frame).  Beyond that, two workgroups per compute
+    // unit are better than one: while one starts or drains a chunk the other keeps streaming.
     const int max_waves_cu = std::min(4 * var->WPE, kLdsPerCu / lds_wave);
+    const int waves_per_pos = d.heads / hpw;
+    const int want = std::min(max_waves_cu, std::max(waves_per_pos, max_waves_cu / 2));
     int wpb = 1;
     for (int cand : {8, 4, 2, 1})
-        if (cand <= max_waves_cu && RG % cand == 0) {
+        if (cand <= want && RG % cand == 0) {
             wpb = cand;
             break;
         }
@@ -87,17 +91,27 @@ bool mfma_plan(dsattn_plan_t &pl)
     const int blocks_cu = std::max(1, max_waves_cu / wpb);
     const int bpc = RG / wpb;
 
-    // chunks per row group: more chunks fill the machine and shorten the tail, fewer chunks
-    // re-read less context (2w boundary frames + G global frames per chunk)
+    // chunks per row group: fewer chunks re-read less context (2w boundary frames + G global
+    // frames of K and V per chunk); more chunks fill the machine.  Model: time ~ traffic x fill,
+    // where the workgroups run in rounds of `slots`.  With few rounds the workgroups stay in
+    // step and a last round less than 85 % full costs a whole round; after about six rounds they have
+    // drifted apart and the tail costs little more than its share.  Fewer workgroups than slots
+    // leave compute units idle.
     const double slots = (double)kCus * blocks_cu;
     int best_nc = 1;
     double best_cost = 1e300;
     for (int nc = 1; nc <= d.n_clips; ++nc) {
         const int m = (d.n_clips + nc - 1) / nc;
         if ((d.n_clips + m - 1) / m != nc) continue;  // same chunking as a smaller nc
-        const double blocks = (double)bpc * nc;
-        const double rounds = std::ceil(blocks / slots);
-        const double fill = rounds * slots / blocks;
+        const double rounds = (double)bpc * nc / slots;
+        const double whole = std::floor(rounds);
+        const double rem = rounds - whole;
+        const double rounds_eff =
+            rounds <= 1.0 ? 1.0
+                          : whole + (rem > 1e-9 ? (whole < 6.0 && rem < 0.85 ? 1.0
+                                                                              : std::max(rem, 0.6))
+                                                : 0.0);
+        const double fill = rounds_eff / rounds;
         const double kv = (16.0 * m + (nc > 1 ? 2.0 * d.local_ctx : 0.0) + G) / (16.0 * m);
         const double cost = (2.0 + 2.0 * kv) / 4.0 * fill;
         if (cost < best_cost - 1e-12) {
