@@ -109,8 +109,9 @@ def main():
     t1 = time.perf_counter()
     wall_ms = (t1 - t0) * 1e3
     ms_per_step = wall_ms / args.steps
-    per_level_ms = [float(np.mean([ev[s][j].elapsed_time(ev[s][j + 1])
-                                   for s in range(args.steps)])) for j in range(n_lv)]
+    lv_times = [[ev[s][j].elapsed_time(ev[s][j + 1]) for s in range(args.steps)]
+                for j in range(n_lv)]
+    per_level_ms = [float(np.mean(t)) for t in lv_times]
 
     qfp = sum(wl.F * L["level"].P for L in levels)
     value = qfp / (ms_per_step * 1e-3)
@@ -142,6 +143,24 @@ def main():
     e1.record(stream)
     torch.cuda.synchronize()
     copy_gbps = 2 * nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    # ---- the materialised context gather (dsattn_gather_context), timed on its own: it is not
+    # on dsattn_forward's path, which gathers by index inside the fused kernel
+    lk = B.dsattn_plan_ctx_max(L0["plan"])
+    kctx = torch.empty((wl.n_clips, lk, L0["level"].P, L0["level"].C), dtype=L0["k"].dtype,
+                       device=dev)
+    B.dsattn_gather_context(L0["plan"], L0["k"], None, kctx, None, stream)
+    g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    g0.record(stream)
+    for _ in range(5):
+        B.dsattn_gather_context(L0["plan"], L0["k"], None, kctx, None, stream)
+    g1.record(stream)
+    torch.cuda.synchronize()
+    gather_ms = g0.elapsed_time(g1) / 5
+    _, ctx_len = B.dsattn_plan_ctx_indices(L0["plan"])
+    gather_bytes = 2 * int(ctx_len.sum()) * L0["level"].P * L0["level"].C * 2  # read + write
+    gather = {"ms_per_tensor": round(gather_ms, 4), "GBps": round(gather_bytes / gather_ms / 1e6, 1),
+              "bytes_per_tensor": gather_bytes}
+    del kctx
     # restore O (the copy probe used it as scratch)
     step()
     torch.cuda.synchronize()
@@ -184,7 +203,10 @@ def main():
         "pct_hbm_roofline": round(100.0 * step_gbps / HBM_PEAK_GBPS, 2),
         "algorithmic_GBps": round(step_gbps, 1),
         "per_level_ms": [round(x, 4) for x in per_level_ms],
+        "launch_ms_min_median": [[round(float(np.min(t)), 4), round(float(np.median(t)), 4)]
+                                 for t in lv_times],
         "copy_probe_GBps": round(copy_gbps, 1),
+        "gather_context": gather,
         "device": torch.cuda.get_device_name(0),
         "roofline": roofline,
         "cpu_baseline": cpu,
