@@ -40,6 +40,8 @@ bool mfma_plan(dsattn_plan_t &pl)
     const dsattn_desc &d = pl.desc;
     if (d.io_dtype != DSATTN_BF16 || d.clip_len != 16) return false;
     if (pl.C % 8 != 0) return false;
+    // the kernel addresses the 16 frame rows of a tile with 32-bit byte offsets
+    if ((int64_t)d.spatial * pl.C * 2 * 16 >= ((int64_t)1 << 32)) return false;
     const int G = (int)pl.global_idx.size();
     // global key tiles: variants exist for 0, 1 and 4 tiles; a partly used tile is masked
     if (G > 64) return false;
