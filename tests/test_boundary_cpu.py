@@ -159,3 +159,62 @@ def test_workload_recipes():
     # frames are strongly correlated, positions are not
     x = q1.float()
     assert (x[0] - x[7]).abs().mean() < 0.3 and (x[:, 0] - x[:, 1]).abs().mean() > 0.5
+
+
+# ---------------------------------------------------------------- launch planner (host logic)
+
+def plan_info(wl, lv, **kw):
+    g = synth.global_idx_for(wl)
+    plan = B.dsattn_plan(wl.clip_len, wl.n_clips, wl.local_ctx, lv.P, lv.heads, lv.head_dim, g,
+                         io_dtype=B.DSATTN_F32 if wl.dtype == "f32" else B.DSATTN_BF16, device=-1,
+                         **kw)
+    info = B.dsattn_plan_launch_info(plan)
+    plan.close()
+    return info
+
+
+def test_planner_choices_per_level():
+    W = synth.WORKLOADS
+    assert plan_info(W["C0"], W["C0"].levels[0])["kernel"] == 0          # fp32: vector-ALU kernel
+    c3 = plan_info(W["C3"], W["C3"].levels[0])
+    assert (c3["kernel"], c3["heads_per_wave"], c3["local_tiles"], c3["global_tiles"]) == (1, 1, 2, 1)
+    assert c3["block_threads"] == 512 and c3["lds_bytes"] <= 160 * 1024
+    assert plan_info(W["C2"], W["C2"].levels[0])["heads_per_wave"] == 2   # 2 x 80 channels per row
+    assert plan_info(W["C1"], W["C1"].levels[0])["heads_per_wave"] == 4   # 4 x 40
+    for lv in W["C4"].levels:                                             # 64 global frames
+        i = plan_info(W["C4"], lv)
+        assert i["kernel"] == 1 and i["global_tiles"] == 4 and i["local_tiles"] == 2
+        assert i["heads_per_wave"] * lv.head_dim <= 160
+    for name in ("C1", "C2", "C3", "C4"):
+        for lv in W[name].levels:
+            i = plan_info(W[name], lv)
+            waves = i["block_threads"] // 64
+            row_groups = lv.P * lv.heads // i["heads_per_wave"]
+            chunks = -(-W[name].n_clips // i["clips_per_task"])
+            assert row_groups % waves == 0
+            assert i["n_tasks"] == row_groups * chunks
+            assert 1 <= i["clips_per_task"] <= W[name].n_clips
+
+
+def test_planner_fallbacks_and_overrides(monkeypatch):
+    W = synth.WORKLOADS
+    lv = W["C3"].levels[0]
+    assert plan_info(W["C3"], lv, flags=B.DSATTN_FLAG_FORCE_GENERIC)["kernel"] == 0
+    monkeypatch.setenv("DSATTN_FORCE_GENERIC", "1")
+    assert plan_info(W["C3"], lv)["kernel"] == 0
+    monkeypatch.delenv("DSATTN_FORCE_GENERIC")
+    monkeypatch.setenv("DSATTN_CLIPS_PER_TASK", "7")
+    monkeypatch.setenv("DSATTN_WAVES_PER_BLOCK", "2")
+    i = plan_info(W["C3"], lv)
+    assert i["clips_per_task"] == 7 and i["block_threads"] == 128
+    assert i["n_tasks"] == 1280 * 21
+    monkeypatch.delenv("DSATTN_CLIPS_PER_TASK")
+    monkeypatch.delenv("DSATTN_WAVES_PER_BLOCK")
+    # shapes without an MFMA variant run the generic kernel
+    for kw in (dict(clip_len=8), dict(head_dim=48), dict(local_ctx=17), dict(n_global=65)):
+        clip_len = kw.get("clip_len", 16)
+        g = list(range(kw.get("n_global", 4)))
+        plan = B.dsattn_plan(clip_len, 8, kw.get("local_ctx", 2), 4, 2, kw.get("head_dim", 160), g,
+                             device=-1)
+        assert B.dsattn_plan_launch_info(plan)["kernel"] == 0, kw
+        plan.close()
