@@ -7,15 +7,16 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "dsattn_oracle.c")
+SRCS = [os.path.join(HERE, "dsattn_oracle.c"), os.path.join(HERE, "groupnorm_oracle.c")]
 LIB = os.path.join(HERE, "liboracle_dsattn.so")
 
 
 def build(force: bool = True) -> str:
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+    if not force and os.path.exists(LIB) and \
+            os.path.getmtime(LIB) >= max(os.path.getmtime(s) for s in SRCS):
         return LIB
     cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-           "-o", LIB, SRC, "-lm"]
+           "-o", LIB, *SRCS, "-lm"]
     subprocess.run(cmd, check=True)
     return LIB
 

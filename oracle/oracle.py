@@ -33,6 +33,8 @@ def _load():
                                        ctypes.c_double, ctypes.c_double, i64, p, p, p, p, p]
         lib.oracle_gather_context.restype = ctypes.c_int
         lib.oracle_gather_context.argtypes = [i64, i64, i64, p, i64, i64, p, p]
+        lib.oracle_groupnorm.restype = ctypes.c_int
+        lib.oracle_groupnorm.argtypes = [i64, i64, i64, i64, i64, ctypes.c_double, p, p, p, p, p, p]
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_num_threads.argtypes = []
         _lib = lib
@@ -113,3 +115,25 @@ def gather_context(x, clip_len, n_clips, w, global_idx):
     if rc != 0:
         raise ValueError(f"oracle_gather_context failed with {rc}")
     return out
+
+
+def groupnorm(x, clip_len, n_clips, groups, eps=1e-5, gamma=None, beta=None):
+    """Clip-parallel group normalisation (Section 4.2): x [F, P, C] -> (y, mean[groups], var[groups]),
+    statistics over the whole video per channel group, computed clip by clip as the paper orders it."""
+    lib = _load()
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    F, P, C = x.shape
+    if F != clip_len * n_clips:
+        raise ValueError("shape mismatch")
+    ga = None if gamma is None else np.ascontiguousarray(gamma, dtype=np.float64)
+    be = None if beta is None else np.ascontiguousarray(beta, dtype=np.float64)
+    y = np.empty_like(x)
+    mean = np.empty((groups,), dtype=np.float64)
+    var = np.empty((groups,), dtype=np.float64)
+    rc = lib.oracle_groupnorm(clip_len, n_clips, P, C, groups, float(eps), x.ctypes.data,
+                              None if ga is None else ga.ctypes.data,
+                              None if be is None else be.ctypes.data, y.ctypes.data,
+                              mean.ctypes.data, var.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"oracle_groupnorm failed with {rc}")
+    return y, mean, var
