@@ -161,6 +161,25 @@ def main():
     gather = {"ms_per_tensor": round(gather_ms, 4), "GBps": round(gather_bytes / gather_ms / 1e6, 1),
               "bytes_per_tensor": gather_bytes}
     del kctx
+    # ---- clip-parallel group normalisation of the same level's tensor (Section 4.2), on its own:
+    # three reads and one write of the tensor (two statistics passes in the paper's order + apply)
+    lvl = L0["level"]
+    gn_groups = 32
+    gn_bytes = B.dsattn_groupnorm_workspace(wl.clip_len, wl.n_clips, lvl.P, lvl.C, gn_groups)
+    gn_ws = torch.empty(gn_bytes // 4 + 1, dtype=torch.float32, device=dev)
+
+    def gn():
+        B.dsattn_groupnorm(wl.clip_len, wl.n_clips, lvl.P, lvl.C, gn_groups, L0["q"], L0["o"], gn_ws,
+                           gn_bytes, stream=stream)
+    gn()
+    g0.record(stream)
+    for _ in range(5):
+        gn()
+    g1.record(stream)
+    torch.cuda.synchronize()
+    gn_ms = g0.elapsed_time(g1) / 5
+    groupnorm = {"ms": round(gn_ms, 4), "GBps": round(4 * nbytes / gn_ms / 1e6, 1),
+                 "algorithmic_bytes": 4 * nbytes, "groups": gn_groups}
     # restore O (the copy probe used it as scratch)
     step()
     torch.cuda.synchronize()
@@ -207,6 +226,7 @@ def main():
                                  for t in lv_times],
         "copy_probe_GBps": round(copy_gbps, 1),
         "gather_context": gather,
+        "groupnorm": groupnorm,
         "device": torch.cuda.get_device_name(0),
         "roofline": roofline,
         "cpu_baseline": cpu,

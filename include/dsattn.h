@@ -31,6 +31,7 @@
 #ifndef DSATTN_H
 #define DSATTN_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -153,6 +154,40 @@ int dsattn_forward_ctx(const dsattn_plan_t *plan, const void *Q, const void *Kct
  * yardstick that achieved bandwidth and profiler byte counters are scaled by.
  */
 int dsattn_copy_probe(void *dst, const void *src, int64_t bytes, void *stream);
+
+/*
+ * Clip-parallel group normalisation (Section 4.2, "Group normalization"): the second temporal
+ * module of the paper that needs context from every clip.  X is [F, P, C] with F = n_clips *
+ * clip_len; the C channels form `groups` contiguous groups.  The statistics of a group are taken
+ * over the whole video in the paper's order: per-clip means -> global mean (mean of the clip
+ * means) -> per-clip mean squared deviation about the GLOBAL mean -> global variance (mean of
+ * those); then  y = (x - mean[g]) / sqrt(var[g] + eps) * gamma[c] + beta[c].
+ */
+typedef struct dsattn_gn_desc {
+    int32_t clip_len;  /* F_clip >= 1 */
+    int32_t n_clips;   /* N >= 1 */
+    int32_t spatial;   /* P >= 1 */
+    int32_t channels;  /* C >= 1 */
+    int32_t groups;    /* divides C; C a multiple of 8 (bf16) / 4 (fp32) and at least that many
+                          channels per group (a 16-byte lane may straddle two groups, not more) */
+    int32_t io_dtype;  /* dsattn_dtype of X and Y; statistics are fp32/fp64 */
+    float eps;         /* >= 0 */
+} dsattn_gn_desc;
+
+/* Bytes of device workspace dsattn_groupnorm needs for this shape (per-clip partial sums). */
+int dsattn_groupnorm_workspace(const dsattn_gn_desc *desc, size_t *bytes);
+
+/*
+ *   X, Y      : device, [F, P, C] of io_dtype, 16-byte aligned; Y may be X (in place)
+ *   gamma,beta: device, [C] fp32, or NULL for 1 / 0
+ *   stats     : device, [2 * groups] fp32 receiving mean[g] then 1/sqrt(var[g] + eps), or NULL
+ *   workspace : device, at least dsattn_groupnorm_workspace() bytes, 16-byte aligned; contents
+ *               are overwritten; calls sharing a workspace must not overlap
+ * Enqueues five kernels on `stream`; allocates nothing.  Errors: EINVAL, EUNSUPPORTED, EHIP.
+ */
+int dsattn_groupnorm(const dsattn_gn_desc *desc, const void *X, const float *gamma,
+                     const float *beta, void *Y, float *stats, void *workspace,
+                     size_t workspace_bytes, void *stream);
 
 /* Static description of a status code; never NULL. */
 const char *dsattn_strerror(int code);

@@ -10,7 +10,8 @@ import importlib
 _BINDING_NAMES = (
     "dsattn_plan", "dsattn_plan_destroy", "dsattn_plan_ctx_max", "dsattn_plan_ctx_indices",
     "dsattn_plan_launch_info", "dsattn_gather_context", "dsattn_forward", "dsattn_forward_ctx",
-    "dsattn_copy_probe", "dsattn_strerror", "dsattn_last_error", "Plan", "DsattnError",
+    "dsattn_copy_probe", "dsattn_strerror", "dsattn_last_error", "dsattn_groupnorm",
+    "dsattn_groupnorm_workspace", "Plan", "DsattnError",
     "DSATTN_F32", "DSATTN_BF16", "DSATTN_FLAG_FORCE_GENERIC", "DSATTN_FLAG_SLIDING_WINDOW",
 )
 

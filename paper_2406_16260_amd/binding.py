@@ -28,7 +28,8 @@ DSATTN_FLAG_SLIDING_WINDOW = 2
 EXPORTS = (
     "dsattn_plan", "dsattn_plan_destroy", "dsattn_plan_ctx_max", "dsattn_plan_ctx_indices",
     "dsattn_plan_launch_info", "dsattn_gather_context", "dsattn_forward", "dsattn_forward_ctx",
-    "dsattn_copy_probe", "dsattn_strerror", "dsattn_last_error",
+    "dsattn_copy_probe", "dsattn_strerror", "dsattn_last_error", "dsattn_groupnorm_workspace",
+    "dsattn_groupnorm",
 )
 
 
@@ -39,6 +40,14 @@ class DsattnDesc(ctypes.Structure):
         ("io_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32), ("scale", ctypes.c_float),
         ("flags", ctypes.c_uint32), ("bias_local", ctypes.c_float), ("bias_global", ctypes.c_float),
         ("window", ctypes.c_int32),
+    ]
+
+
+class DsattnGnDesc(ctypes.Structure):
+    _fields_ = [
+        ("clip_len", ctypes.c_int32), ("n_clips", ctypes.c_int32), ("spatial", ctypes.c_int32),
+        ("channels", ctypes.c_int32), ("groups", ctypes.c_int32), ("io_dtype", ctypes.c_int32),
+        ("eps", ctypes.c_float),
     ]
 
 
@@ -97,6 +106,12 @@ def load():
     lib.dsattn_forward_ctx.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.dsattn_copy_probe.restype = ctypes.c_int
     lib.dsattn_copy_probe.argtypes = [vp, vp, ctypes.c_int64, vp]
+    lib.dsattn_groupnorm_workspace.restype = ctypes.c_int
+    lib.dsattn_groupnorm_workspace.argtypes = [ctypes.POINTER(DsattnGnDesc),
+                                               ctypes.POINTER(ctypes.c_size_t)]
+    lib.dsattn_groupnorm.restype = ctypes.c_int
+    lib.dsattn_groupnorm.argtypes = [ctypes.POINTER(DsattnGnDesc), vp, vp, vp, vp, vp, vp,
+                                     ctypes.c_size_t, vp]
     lib.dsattn_strerror.restype = ctypes.c_char_p
     lib.dsattn_strerror.argtypes = [ctypes.c_int]
     lib.dsattn_last_error.restype = ctypes.c_char_p
@@ -234,3 +249,21 @@ def dsattn_strerror(code: int) -> str:
 
 def dsattn_last_error() -> str:
     return load().dsattn_last_error().decode()
+
+
+def dsattn_groupnorm_workspace(clip_len, n_clips, spatial, channels, groups, io_dtype=DSATTN_BF16,
+                               eps=1e-5) -> int:
+    desc = DsattnGnDesc(clip_len, n_clips, spatial, channels, groups, io_dtype, float(eps))
+    out = ctypes.c_size_t()
+    _check(load().dsattn_groupnorm_workspace(ctypes.byref(desc), ctypes.byref(out)),
+           "dsattn_groupnorm_workspace")
+    return int(out.value)
+
+
+def dsattn_groupnorm(clip_len, n_clips, spatial, channels, groups, X, Y, workspace,
+                     workspace_bytes, gamma=None, beta=None, stats=None, io_dtype=DSATTN_BF16,
+                     eps=1e-5, stream=None):
+    desc = DsattnGnDesc(clip_len, n_clips, spatial, channels, groups, io_dtype, float(eps))
+    _check(load().dsattn_groupnorm(ctypes.byref(desc), _ptr(X), _ptr(gamma), _ptr(beta), _ptr(Y),
+                                   _ptr(stats), _ptr(workspace), int(workspace_bytes),
+                                   _stream(stream)), "dsattn_groupnorm")

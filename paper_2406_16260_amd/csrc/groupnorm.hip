@@ -1,0 +1,327 @@
+// Clip-parallel group normalisation (Section 4.2, "Group normalization") for one GPU that holds
+// every clip: the statistics of a channel group are those of the whole video, computed in the
+// paper's order (per-clip means -> global mean -> per-clip squared deviations about the global
+// mean -> global variance), then y = (x - mean) * rstd * gamma + beta.
+//
+// All kernels stream X ([F, P, C], C fastest) with 16-byte lanes; a lane's 16 bytes belong to one
+// group.  Reductions are deterministic: per-thread fp32 sums, a fixed-order sum per workgroup into
+// a partial-sum table in the caller's workspace, and a small finalising kernel in fp64.
+#include <hip/hip_bf16.h>
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+
+#include "plan.h"
+
+namespace dsattn {
+
+namespace {
+
+struct GnShape {
+    int vec;        // elements per 16-byte lane
+    int ch;         // lanes per row = C / vec
+    int cg;         // channels per group
+    int rpb;        // rows handled together by a workgroup (blockDim.y)
+    int bpc;        // workgroups per clip
+    int64_t rows_per_clip;
+    int64_t rows_per_block;
+};
+
+bool gn_shape(const dsattn_gn_desc &d, GnShape &s)
+{
+    s.vec = d.io_dtype == DSATTN_BF16 ? 8 : 4;
+    if (d.channels % d.groups != 0 || d.channels % s.vec != 0) return false;
+    s.cg = d.channels / d.groups;
+    // a 16-byte lane may straddle two groups, not more
+    if (s.cg < s.vec && s.vec % s.cg != 0) return false;
+    if (s.cg < s.vec) return false;
+    s.ch = d.channels / s.vec;
+    if (s.ch > 1024) return false;
+    s.rpb = std::max(1, 512 / s.ch);
+    s.rows_per_clip = (int64_t)d.clip_len * d.spatial;
+    // about eight workgroups per compute unit over the whole tensor, at least one per clip
+    const int64_t want = std::max<int64_t>(1, (256 * 8) / d.n_clips);
+    const int64_t max_bpc = std::max<int64_t>(1, s.rows_per_clip / (4 * s.rpb));
+    s.bpc = (int)std::min<int64_t>(want, max_bpc);
+    s.rows_per_block = (s.rows_per_clip + s.bpc - 1) / s.bpc;
+    return true;
+}
+
+__device__ inline void unpack(const uint4 &v, float (&x)[8], __hip_bfloat16 *)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        x[2 * i] = __uint_as_float(w[i] << 16);
+        x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+__device__ inline void unpack(const uint4 &v, float (&x)[8], float *)
+{
+    x[0] = __uint_as_float(v.x);
+    x[1] = __uint_as_float(v.y);
+    x[2] = __uint_as_float(v.z);
+    x[3] = __uint_as_float(v.w);
+}
+
+// Pass 1 (SQDEV = false): per-clip sums.  Pass 2 (SQDEV = true): per-clip sums of squared
+// deviations about the global mean.  blockIdx = (workgroup within clip, clip);
+// thread (x, y) = (lane of the row, row phase).  A lane's VEC channels lie in group g0 (the
+// first `split` of them) and, when the lane straddles a boundary, in group g0 + 1.
+// partial is [N][bpc][groups].
+template <typename T, bool SQDEV>
+__global__ __launch_bounds__(1024) void gn_partial_kernel(const uint4 *__restrict__ X,
+                                                          const float *__restrict__ mean,
+                                                          float *__restrict__ partial, int ch,
+                                                          int cg, int groups,
+                                                          int64_t rows_per_clip,
+                                                          int64_t rows_per_block)
+{
+    constexpr int VEC = sizeof(T) == 2 ? 8 : 4;
+    constexpr int UNR = 4;  // independent row loads in flight per thread
+    extern __shared__ float red[];  // [2][blockDim.y][ch]: sums for g0, then for g0 + 1
+    const int lane = threadIdx.x, ry = threadIdx.y, ny = blockDim.y;
+    const int clip = blockIdx.y;
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t r1 = min(rows_per_clip, r0 + rows_per_block);
+    const int g0 = (lane * VEC) / cg;
+    const int split = min(VEC, (g0 + 1) * cg - lane * VEC);
+    const float mu0 = SQDEV ? mean[g0] : 0.f;
+    const float mu1 = SQDEV && split < VEC ? mean[g0 + 1] : 0.f;
+    float acc0 = 0.f, acc1 = 0.f;
+    const uint4 *base = X + (int64_t)clip * rows_per_clip * ch + lane;
+    auto add_row = [&](const uint4 &v) __attribute__((always_inline)) {
+        float x[8];
+        unpack(v, x, (T *)nullptr);
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            const bool lo = i < split;
+            const float d = x[i] - (lo ? mu0 : mu1);
+            const float t = SQDEV ? d * d : x[i];
+            s0 += lo ? t : 0.f;
+            s1 += lo ? 0.f : t;
+        }
+        acc0 += s0;
+        acc1 += s1;
+    };
+    int64_t r = r0 + ry;
+    for (; r + (int64_t)(UNR - 1) * ny < r1; r += (int64_t)UNR * ny) {
+        uint4 v[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) v[u] = base[(r + (int64_t)u * ny) * ch];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) add_row(v[u]);
+    }
+    for (; r < r1; r += ny) add_row(base[r * ch]);
+
+    float *red0 = red, *red1 = red + ny * ch;
+    red0[ry * ch + lane] = acc0;
+    red1[ry * ch + lane] = acc1;
+    __syncthreads();
+    // one thread per group adds, in a fixed order, the lanes that hold its channels
+    const int t = ry * ch + lane;
+    if (t < groups) {
+        const int g = t;
+        const int l0 = (g * cg) / VEC, l1 = ((g + 1) * cg - 1) / VEC;
+        float s = 0.f;
+        for (int y = 0; y < ny; ++y)
+            for (int l = l0; l <= l1; ++l) {
+                const int lg0 = (l * VEC) / cg;
+                if (lg0 == g) s += red0[y * ch + l];
+                if (lg0 == g - 1) s += red1[y * ch + l];
+            }
+        partial[((int64_t)clip * gridDim.x + blockIdx.x) * groups + g] = s;
+    }
+}
+
+// One workgroup per group.  MODE 0: stats[g] = mean of the clip means.  MODE 1:
+// stats[groups + g] = 1 / sqrt(mean of the per-clip mean squared deviations + eps).
+// Clips are equally long, so "the mean over clips of (clip sum / clip size)" is taken as the
+// sum of all partials over (clip size x number of clips), in fp64 and in a fixed order.
+template <int MODE>
+__global__ __launch_bounds__(256) void gn_finalize_kernel(const float *__restrict__ partial,
+                                                          float *__restrict__ stats, int n_clips,
+                                                          int bpc, int groups, double n_clip_elems,
+                                                          float eps)
+{
+    __shared__ double red[256];
+    const int g = blockIdx.x;
+    const int64_t n = (int64_t)n_clips * bpc;
+    double s = 0.0;
+    for (int64_t i = threadIdx.x; i < n; i += 256) s += (double)partial[i * groups + g];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const double v = red[0] / n_clip_elems / (double)n_clips;
+        if (MODE == 0)
+            stats[g] = (float)v;
+        else
+            stats[groups + g] = (float)(1.0 / sqrt(v + (double)eps));
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gn_apply_kernel(const uint4 *__restrict__ X,
+                                                       uint4 *__restrict__ Y,
+                                                       const float *__restrict__ stats,
+                                                       const float *__restrict__ gamma,
+                                                       const float *__restrict__ beta, int ch,
+                                                       int cg, int groups, int64_t n16)
+{
+    constexpr int VEC = sizeof(T) == 2 ? 8 : 4;
+    constexpr int UNR = 4;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    auto one = [&](int64_t i, const uint4 &v) __attribute__((always_inline)) {
+        const int lane = (int)(i % ch);
+        const int g0 = (lane * VEC) / cg;
+        const int split = min(VEC, (g0 + 1) * cg - lane * VEC);
+        const float mu0 = stats[g0], rs0 = stats[groups + g0];
+        const float mu1 = split < VEC ? stats[g0 + 1] : 0.f;
+        const float rs1 = split < VEC ? stats[groups + g0 + 1] : 0.f;
+        float x[8];
+        unpack(v, x, (T *)nullptr);
+        float y[8];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            const int c = lane * VEC + k;
+            const float ga = gamma ? gamma[c] : 1.f;
+            const float be = beta ? beta[c] : 0.f;
+            const bool lo = k < split;
+            y[k] = (x[k] - (lo ? mu0 : mu1)) * (lo ? rs0 : rs1) * ga + be;
+        }
+        uint4 o;
+        if constexpr (sizeof(T) == 2) {
+            uint32_t w[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const __hip_bfloat16 lo = __float2bfloat16(y[2 * k]);      // RNE
+                const __hip_bfloat16 hi = __float2bfloat16(y[2 * k + 1]);
+                w[k] = (uint32_t)__builtin_bit_cast(unsigned short, lo) |
+                       ((uint32_t)__builtin_bit_cast(unsigned short, hi) << 16);
+            }
+            o = make_uint4(w[0], w[1], w[2], w[3]);
+        } else {
+            o = make_uint4(__float_as_uint(y[0]), __float_as_uint(y[1]), __float_as_uint(y[2]),
+                           __float_as_uint(y[3]));
+        }
+        Y[i] = o;
+    };
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + (UNR - 1) * stride < n16; i += UNR * stride) {
+        uint4 v[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) v[u] = X[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) one(i + u * stride, v[u]);
+    }
+    for (; i < n16; i += stride) one(i, X[i]);
+}
+
+int gn_validate(const dsattn_gn_desc *d, GnShape &s, const char *who)
+{
+    if (!d) return fail(DSATTN_EINVAL, "%s: null descriptor", who);
+    if (d->clip_len < 1 || d->n_clips < 1 || d->spatial < 1 || d->channels < 1 || d->groups < 1)
+        return fail(DSATTN_EINVAL, "%s: sizes must be positive", who);
+    if (d->io_dtype != DSATTN_F32 && d->io_dtype != DSATTN_BF16)
+        return fail(DSATTN_EINVAL, "%s: unknown dtype", who);
+    if (!(d->eps >= 0.f) || std::isinf(d->eps))
+        return fail(DSATTN_EINVAL, "%s: eps must be finite and >= 0", who);
+    if (d->channels % d->groups != 0)
+        return fail(DSATTN_EINVAL, "%s: channels must split evenly into groups", who);
+    if ((int64_t)d->clip_len * d->n_clips * d->spatial * d->channels > ((int64_t)1 << 40) ||
+        d->n_clips > 65535)
+        return fail(DSATTN_EINVAL, "%s: problem too large", who);
+    if (!gn_shape(*d, s))
+        return fail(DSATTN_EUNSUPPORTED,
+                    "%s: need channels %% %d == 0, channels per group >= %d and channels <= %d", who,
+                    d->io_dtype == DSATTN_BF16 ? 8 : 4, d->io_dtype == DSATTN_BF16 ? 8 : 4,
+                    d->io_dtype == DSATTN_BF16 ? 8192 : 4096);
+    return DSATTN_OK;
+}
+
+size_t gn_workspace_bytes(const dsattn_gn_desc &d, const GnShape &s)
+{
+    // partial sums [N][bpc][groups] + statistics [2 * groups] (mean, then 1/sqrt(var + eps))
+    return ((size_t)d.n_clips * s.bpc * d.groups + 2 * (size_t)d.groups) * sizeof(float);
+}
+
+}  // namespace
+}  // namespace dsattn
+
+using namespace dsattn;
+
+extern "C" {
+
+int dsattn_groupnorm_workspace(const dsattn_gn_desc *desc, size_t *bytes)
+{
+    GnShape s;
+    if (!bytes) return fail(DSATTN_EINVAL, "dsattn_groupnorm_workspace: null argument");
+    const int rc = gn_validate(desc, s, "dsattn_groupnorm_workspace");
+    if (rc != DSATTN_OK) return rc;
+    *bytes = gn_workspace_bytes(*desc, s);
+    return DSATTN_OK;
+}
+
+int dsattn_groupnorm(const dsattn_gn_desc *desc, const void *X, const float *gamma,
+                     const float *beta, void *Y, float *stats, void *workspace,
+                     size_t workspace_bytes, void *stream)
+{
+    GnShape s;
+    const int rc = gn_validate(desc, s, "dsattn_groupnorm");
+    if (rc != DSATTN_OK) return rc;
+    const dsattn_gn_desc &d = *desc;
+    if (!X || !Y || !workspace) return fail(DSATTN_EINVAL, "dsattn_groupnorm: null pointer");
+    if (((uintptr_t)X | (uintptr_t)Y | (uintptr_t)workspace) & 15u)
+        return fail(DSATTN_EINVAL, "dsattn_groupnorm: pointers must be 16-byte aligned");
+    if (workspace_bytes < gn_workspace_bytes(d, s))
+        return fail(DSATTN_EINVAL, "dsattn_groupnorm: workspace too small (%zu < %zu bytes)",
+                    workspace_bytes, gn_workspace_bytes(d, s));
+
+    hipStream_t st = (hipStream_t)stream;
+    float *partial = (float *)workspace;
+    float *wstats = partial + (size_t)d.n_clips * s.bpc * d.groups;
+    const dim3 grid(s.bpc, d.n_clips), block(s.ch, s.rpb);
+    const size_t lds = 2 * (size_t)s.ch * s.rpb * sizeof(float);
+    const double n_clip_elems = (double)s.rows_per_clip * (d.channels / d.groups);
+    const int64_t n16 = (int64_t)d.clip_len * d.n_clips * d.spatial * s.ch;
+    int64_t ablocks = (n16 + 256 * 8 - 1) / (256 * 8);
+    ablocks = std::max<int64_t>(1, std::min<int64_t>(ablocks, 1 << 20));
+
+#define DSATTN_GN_RUN(T)                                                                          \
+    do {                                                                                          \
+        hipLaunchKernelGGL((gn_partial_kernel<T, false>), grid, block, lds, st, (const uint4 *)X, \
+                           (const float *)nullptr, partial, s.ch, s.cg, d.groups,                \
+                           s.rows_per_clip, s.rows_per_block);                                    \
+        hipLaunchKernelGGL(gn_finalize_kernel<0>, dim3(d.groups), dim3(256), 0, st, partial,      \
+                           wstats,                                                                \
+                           d.n_clips, s.bpc, d.groups, n_clip_elems, d.eps);                      \
+        hipLaunchKernelGGL((gn_partial_kernel<T, true>), grid, block, lds, st, (const uint4 *)X,  \
+                           (const float *)wstats, partial, s.ch, s.cg, d.groups,                 \
+                           s.rows_per_clip, s.rows_per_block);                                    \
+        hipLaunchKernelGGL(gn_finalize_kernel<1>, dim3(d.groups), dim3(256), 0, st, partial,      \
+                           wstats,                                                                \
+                           d.n_clips, s.bpc, d.groups, n_clip_elems, d.eps);                      \
+        hipLaunchKernelGGL(gn_apply_kernel<T>, dim3((unsigned)ablocks), dim3(256), 0, st,         \
+                           (const uint4 *)X, (uint4 *)Y, (const float *)wstats, gamma, beta,      \
+                           s.ch, s.cg, d.groups, n16);                                           \
+    } while (0)
+    if (d.io_dtype == DSATTN_BF16)
+        DSATTN_GN_RUN(__hip_bfloat16);
+    else
+        DSATTN_GN_RUN(float);
+#undef DSATTN_GN_RUN
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && stats)
+        e = hipMemcpyAsync(stats, wstats, 2 * (size_t)d.groups * sizeof(float),
+                           hipMemcpyDeviceToDevice, st);
+    if (e != hipSuccess) return fail(DSATTN_EHIP, "dsattn_groupnorm: %s", hipGetErrorString(e));
+    return DSATTN_OK;
+}
+
+}  // extern "C"
