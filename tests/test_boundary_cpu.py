@@ -218,3 +218,17 @@ def test_planner_fallbacks_and_overrides(monkeypatch):
                              device=-1)
         assert B.dsattn_plan_launch_info(plan)["kernel"] == 0, kw
         plan.close()
+
+
+def test_header_is_plain_c_and_usable_from_c(tmp_path):
+    """include/dsattn.h compiles as C99 with warnings as errors, and a C program linked against
+    libdsattn.so drives the host-side entry points."""
+    import subprocess
+    exe = tmp_path / "host_only_plan"
+    src = os.path.join(ROOT, "tests", "c_abi", "host_only_plan.c")
+    libdir = os.path.dirname(B.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic",
+                    "-I", os.path.join(ROOT, "include"), src, "-o", str(exe),
+                    "-L", libdir, "-l:libdsattn.so", f"-Wl,-rpath,{libdir}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+    assert out.startswith("ok lk_max=7")
