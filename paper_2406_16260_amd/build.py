@@ -13,8 +13,9 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdsattn.so")
 
-SOURCES = ["dsattn_api.hip", "kernels_generic.hip", "kernel_mfma.hip", "mfma_d160.hip", "mfma_d80.hip",
-           "mfma_d40.hip", "groupnorm.hip"]
+SOURCES = ["mfma_d40.hip", "mfma_d32.hip", "mfma_d96.hip", "mfma_d80.hip", "mfma_d64.hip",
+           "mfma_d160.hip", "mfma_d128.hip", "dsattn_api.hip", "kernels_generic.hip",
+           "kernel_mfma.hip", "groupnorm.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -34,7 +35,7 @@ def _compile(src: str, extra) -> str:
 
 def build(extra_flags=(), verbose=False) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(7, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     subprocess.run(cmd, check=True)

@@ -14,16 +14,21 @@ namespace {
 constexpr int kLdsPerCu = 160 * 1024;  // gfx950 LDS per compute unit, also the per-workgroup cap
 constexpr int kCus = 256;
 
+typedef const MfmaVariant *(*VariantTable)(int *);
+const VariantTable kTables[] = {mfma_variants_d160, mfma_variants_d128, mfma_variants_d96,
+                                mfma_variants_d80,  mfma_variants_d64,  mfma_variants_d40,
+                                mfma_variants_d32};
+
 const MfmaVariant *find_variant(int D, int HPW, int NLT, int NGT, bool out_f32)
 {
-    int n = 0;
-    const MfmaVariant *v = nullptr;
-    if (D == 160) v = mfma_variants_d160(&n);
-    else if (D == 80) v = mfma_variants_d80(&n);
-    else if (D == 40) v = mfma_variants_d40(&n);
-    for (int i = 0; i < n; ++i)
-        if (v[i].HPW == HPW && v[i].NLT == NLT && v[i].NGT == NGT && v[i].out_f32 == out_f32)
-            return &v[i];
+    for (VariantTable tab : kTables) {
+        int n = 0;
+        const MfmaVariant *v = tab(&n);
+        for (int i = 0; i < n; ++i)
+            if (v[i].D == D && v[i].HPW == HPW && v[i].NLT == NLT && v[i].NGT == NGT &&
+                v[i].out_f32 == out_f32)
+                return &v[i];
+    }
     return nullptr;
 }
 

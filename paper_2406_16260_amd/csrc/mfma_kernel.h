@@ -16,9 +16,14 @@
 //     the neighbouring clips (c_pre / c_post of Section 4.1) are reused on chip.
 //   * The next clip's Q/K/V rows are in flight in registers while the current clip is computed.
 // Per clip and head:  S^T = K Q^T  (16x16x32 bf16 MFMA, keys on M, the 16 query frames on N),
-// fp32 softmax over keys (in-lane plus two cross-lane steps), P^T rounded to bf16 and fed
-// straight back as the B operand of  O^T = V^T P^T  (16x16x16 bf16 MFMA).  V^T operands are made
-// from row-major V rows with an MFMA against a 0/1 selector matrix, which is exact.
+// fp32 softmax over keys (maximum: in-lane plus two cross-lane steps; weights exp2 with the scale
+// folded in), P^T rounded to bf16 and fed straight back as the B operand of  O^T = V^T P^T
+// (16x16x16 bf16 MFMA).  The denominator is the sum of the rounded weights, taken by one more MFMA
+// with an all-ones A operand.  V^T operands are made from row-major V rows with an MFMA against a
+// 0/1 selector matrix, which is exact.
+// Options of the scopes: the biases of the two scopes' logits enter as one shift of the raw global
+// scores (a softmax sees only their difference); a sliding window |key frame - query frame| <= r
+// on the local scope is a per-lane mask on the local scores.
 //
 // LDS regions are private to a wavefront; the barrier orders nothing, it only paces.
 #pragma once
@@ -466,12 +471,26 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
 
 // Variant tables, one translation unit per head_dim.
 const MfmaVariant *mfma_variants_d160(int *n);
+const MfmaVariant *mfma_variants_d128(int *n);
+const MfmaVariant *mfma_variants_d96(int *n);
 const MfmaVariant *mfma_variants_d80(int *n);
+const MfmaVariant *mfma_variants_d64(int *n);
 const MfmaVariant *mfma_variants_d40(int *n);
+const MfmaVariant *mfma_variants_d32(int *n);
 
 #define DSATTN_MFMA_VARIANT(D, HPW, NLT, NGT, WPE)                                             \
     {D, HPW, NLT, NGT, WPE, false,                                                             \
      (const void *)&dsattn_mfma_kernel<D, HPW, NLT, NGT, WPE, false>},                         \
     {D, HPW, NLT, NGT, WPE, true, (const void *)&dsattn_mfma_kernel<D, HPW, NLT, NGT, WPE, true>}
+
+// local context 0..16 frames (1 to 3 local key tiles), no or one global key tile
+#define DSATTN_MFMA_SET(D, HPW, WPE)                                                           \
+    DSATTN_MFMA_VARIANT(D, HPW, 1, 0, WPE), DSATTN_MFMA_VARIANT(D, HPW, 1, 1, WPE),            \
+    DSATTN_MFMA_VARIANT(D, HPW, 2, 0, WPE), DSATTN_MFMA_VARIANT(D, HPW, 2, 1, WPE),            \
+    DSATTN_MFMA_VARIANT(D, HPW, 3, 0, WPE), DSATTN_MFMA_VARIANT(D, HPW, 3, 1, WPE)
+
+// four global key tiles, local context 0..8 frames
+#define DSATTN_MFMA_SET_G4(D, HPW, WPE)                                                        \
+    DSATTN_MFMA_VARIANT(D, HPW, 1, 4, WPE), DSATTN_MFMA_VARIANT(D, HPW, 2, 4, WPE)
 
 }  // namespace dsattn

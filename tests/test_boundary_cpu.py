@@ -220,6 +220,24 @@ def test_planner_fallbacks_and_overrides(monkeypatch):
         plan.close()
 
 
+@pytest.mark.parametrize("D,h,G,hpw", [
+    (128, 8, 16, 1), (96, 8, 16, 2), (96, 5, 16, 1), (64, 8, 16, 2), (64, 3, 0, 1), (32, 8, 16, 4),
+    (32, 6, 16, 2), (32, 7, 3, 1), (40, 6, 16, 2), (40, 5, 16, 1), (80, 3, 16, 1),
+    # 17..64 global frames: fewer heads per wavefront so that the global context fits in registers
+    (128, 4, 64, 1), (96, 4, 33, 1), (64, 4, 64, 1), (32, 8, 64, 2), (32, 3, 64, 1), (40, 7, 17, 1),
+])
+def test_planner_head_dims_and_heads_per_wave(D, h, G, hpw):
+    """Every supported head_dim has an MFMA variant for any head count: the planner takes the
+    widest rows (most heads per wavefront) that divide the head count."""
+    plan = B.dsattn_plan(16, 8, 4, 6, h, D, list(range(0, 2 * G, 2)), device=-1)
+    i = B.dsattn_plan_launch_info(plan)
+    plan.close()
+    assert i["kernel"] == 1 and i["heads_per_wave"] == hpw, i
+    assert i["global_tiles"] == (0 if G == 0 else 1 if G <= 16 else 4)
+    assert i["n_tasks"] % (i["block_threads"] // 64) == 0
+    assert i["lds_bytes"] <= 160 * 1024
+
+
 def test_header_is_plain_c_and_usable_from_c(tmp_path):
     """include/dsattn.h compiles as C99 with warnings as errors, and a C program linked against
     libdsattn.so drives the host-side entry points."""

@@ -255,6 +255,28 @@ def test_mfma_other_head_dims(D, h, P, w, G):
     assert info["heads_per_wave"] == 160 // D
 
 
+@pytest.mark.parametrize("D,h,P,hpw", [
+    (128, 8, 3, 1), (128, 1, 2, 1), (96, 4, 3, 2), (96, 3, 2, 1), (64, 8, 5, 2), (64, 5, 2, 1),
+    (32, 8, 3, 4), (32, 6, 3, 2), (32, 3, 5, 1), (40, 6, 3, 2), (40, 3, 2, 1), (80, 3, 3, 1)])
+@pytest.mark.parametrize("w,G", [(2, 16), (0, 0), (8, 5), (12, 16)])
+def test_mfma_head_dim_family(D, h, P, hpw, w, G):
+    # head dims whose contraction blocks and output tiles are whole (32, 64, 96, 128), and head
+    # counts that the widest rows do not divide: narrower rows, down to one head per wavefront
+    g = synth.stride_global_idx(64, G) if G else []
+    info = run_mfma_case(4, w, P, h, D, g, gen="iid", clips_per_task=3, out_dtypes=("bf16",),
+                         what=f"D={D} h={h}")
+    assert info["heads_per_wave"] == hpw
+
+
+@pytest.mark.parametrize("D,h,P", [(128, 2, 3), (96, 2, 2), (64, 4, 3), (32, 8, 2), (32, 3, 2),
+                                   (40, 3, 2)])
+@pytest.mark.parametrize("w,G", [(4, 64), (0, 17)])
+def test_mfma_head_dim_family_many_global_frames(D, h, P, w, G):
+    g = synth.random_sorted_global_idx(80, G, seed=5)
+    info = run_mfma_case(5, w, P, h, D, g, gen="iid", clips_per_task=2, what=f"G={G} D={D}")
+    assert info["global_tiles"] == 4
+
+
 @pytest.mark.parametrize("D,h,P", [(160, 8, 3), (80, 8, 3), (40, 8, 3), (160, 1, 2)])
 @pytest.mark.parametrize("w,G", [(4, 64), (2, 33), (0, 17), (8, 48)])
 def test_mfma_many_global_frames(D, h, P, w, G):
@@ -460,9 +482,9 @@ def test_randomised_shapes_against_oracle():
     # seeded sweep over shapes the planner sends to either kernel
     rng = np.random.default_rng(2024)
     for case in range(24):
-        D = int(rng.choice([40, 80, 160, 24, 64]))
+        D = int(rng.choice([40, 80, 160, 24, 64, 128]))
         h = int(rng.choice([1, 2, 4, 8]))
-        clip_len = 16 if D in (40, 80, 160) and rng.random() < 0.8 else int(rng.integers(1, 20))
+        clip_len = 16 if D != 24 and rng.random() < 0.8 else int(rng.integers(1, 20))
         n_clips = int(rng.integers(1, 7))
         F = clip_len * n_clips
         w = int(rng.integers(0, 18))
@@ -477,10 +499,8 @@ def test_randomised_shapes_against_oracle():
         ref = U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g, window=window, bias_global=bg)
         o, info = U.library_forward(q, k, v, clip_len, n_clips, w, h, g, out_dtype="f32",
                                     window=window, bias_global=bg)
-        # MFMA variants: clip length 16, head_dim 40/80/160, w <= 16 with up to 16 global frames
-        # (160/D heads per wavefront), w <= 8 with 17..64 (80/D heads per wavefront, 1 at D = 160)
-        expect_mfma = clip_len == 16 and D in (40, 80, 160) and \
-            ((w <= 16 and h % (160 // D) == 0) if G <= 16 else
-             (w <= 8 and (D == 160 or h % (80 // D) == 0)))
+        # MFMA variants: clip length 16, head_dim 32/40/64/80/96/128/160 with any head count,
+        # w <= 16 with up to 16 global frames, w <= 8 with 17..64
+        expect_mfma = clip_len == 16 and D != 24 and (w <= 16 if G <= 16 else w <= 8)
         assert info["kernel"] == (1 if expect_mfma else 0), (info, case)
         U.assert_parity(o, ref, "f32", what=f"random case {case}")
