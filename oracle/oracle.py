@@ -35,6 +35,8 @@ def _load():
         lib.oracle_gather_context.argtypes = [i64, i64, i64, p, i64, i64, p, p]
         lib.oracle_groupnorm.restype = ctypes.c_int
         lib.oracle_groupnorm.argtypes = [i64, i64, i64, i64, i64, ctypes.c_double, p, p, p, p, p, p]
+        lib.oracle_temporal_conv.restype = ctypes.c_int
+        lib.oracle_temporal_conv.argtypes = [i64, i64, i64, i64, i64, i64, p, p, p, p]
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_num_threads.argtypes = []
         _lib = lib
@@ -137,3 +139,26 @@ def groupnorm(x, clip_len, n_clips, groups, eps=1e-5, gamma=None, beta=None):
     if rc != 0:
         raise ValueError(f"oracle_groupnorm failed with {rc}")
     return y, mean, var
+
+
+def temporal_conv(x, w, clip_len, n_clips, bias=None):
+    """Clip-parallel temporal convolution (Section 4.2): x [F, P, C_in], w [2n+1, C_out, C_in]
+    (tap t looks at frame a + t - n), bias [C_out] or None -> y [F, P, C_out] float64.  Every clip
+    is convolved on its own, padded with n frames of each neighbouring clip (zeros at the ends)."""
+    lib = _load()
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    F, P, c_in = x.shape
+    taps, c_out, c_in_w = w.shape
+    if F != clip_len * n_clips or c_in_w != c_in or taps % 2 != 1:
+        raise ValueError("shape mismatch")
+    b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float64)
+    if b is not None and b.shape != (c_out,):
+        raise ValueError("bias shape")
+    y = np.empty((F, P, c_out), dtype=np.float64)
+    rc = lib.oracle_temporal_conv(clip_len, n_clips, P, c_in, c_out, taps // 2, x.ctypes.data,
+                                  w.ctypes.data, None if b is None else b.ctypes.data,
+                                  y.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"oracle_temporal_conv failed with {rc}")
+    return y
