@@ -189,6 +189,56 @@ int dsattn_groupnorm(const dsattn_gn_desc *desc, const void *X, const float *gam
                      const float *beta, void *Y, float *stats, void *workspace,
                      size_t workspace_bytes, void *stream);
 
+/*
+ * Clip-parallel temporal convolution (Section 4.2, "Convolution module"): the third temporal
+ * module of the paper.  X is [F, P, c_in] with F = n_clips * clip_len; the module convolves
+ * along the frame axis only, at every position separately, mixing channels densely:
+ *   Y[f][p][co] = bias[co] + sum_{t = 0 .. 2n} sum_{ci} W[t][co][ci] * X[f + t - n][p][ci]
+ * with frames outside [0, F) read as zeros.  This is what the paper's scheme computes clip by
+ * clip: clip i is padded with c_pre = the last n frames of clip i-1 and c_post = the first n
+ * frames of clip i+1 (zero frames at the two ends of the video), which is why n <= clip_len is
+ * required.  Tap t looks at frame f + t - n (cross-correlation, the deep-learning convention).
+ */
+typedef struct dsattn_conv_desc {
+    int32_t clip_len;  /* F_clip >= 1 */
+    int32_t n_clips;   /* N >= 1 */
+    int32_t spatial;   /* P >= 1 */
+    int32_t c_in;      /* input channels >= 1 */
+    int32_t c_out;     /* output channels >= 1 */
+    int32_t reach;     /* n: frames the kernel reaches to each side (2n + 1 taps), 0 <= n <= F_clip */
+    int32_t io_dtype;  /* dsattn_dtype of X and W; products are accumulated in fp32 */
+    int32_t out_dtype; /* dsattn_dtype of Y; DSATTN_F32 is allowed with bf16 inputs */
+    uint32_t flags;    /* DSATTN_FLAG_FORCE_GENERIC or 0 */
+} dsattn_conv_desc;
+
+/* The launch the library would make for this shape (host only; for tests and benchmarks). */
+typedef struct dsattn_conv_info {
+    int32_t kernel;        /* 0 = generic vector-ALU kernel, 1 = bf16 MFMA implicit-GEMM kernel */
+    int32_t tile_m;        /* output rows (frame, position) per workgroup, 0 for the generic kernel */
+    int32_t tile_n;        /* output channels per workgroup */
+    int32_t tile_k;        /* contraction depth per step */
+    int32_t n_blocks;      /* workgroups launched */
+    int32_t block_threads;
+    int32_t lds_bytes;
+    int32_t reserved;
+    int64_t useful_flops;  /* 2 * P * c_in * c_out * (number of (frame, tap) pairs inside the video) */
+    int64_t algorithmic_bytes; /* X read once + W read once + Y written once */
+} dsattn_conv_info;
+
+int dsattn_temporal_conv_info(const dsattn_conv_desc *desc, dsattn_conv_info *info);
+
+/*
+ *   X    : device, [F, P, c_in] of io_dtype, 16-byte aligned
+ *   W    : device, [2n + 1][c_out][c_in] of io_dtype, 16-byte aligned (c_in fastest)
+ *   bias : device, [c_out] fp32, or NULL for none
+ *   Y    : device, [F, P, c_out] of out_dtype, 16-byte aligned; must not overlap X
+ * Runs on the current device; enqueues one kernel on `stream`; allocates nothing.  bf16 inputs
+ * with c_in a multiple of 8 run on the matrix cores, everything else on a plain vector kernel.
+ * Errors: EINVAL (bad shape, null or misaligned pointer, overlap), EHIP.
+ */
+int dsattn_temporal_conv(const dsattn_conv_desc *desc, const void *X, const void *W,
+                         const float *bias, void *Y, void *stream);
+
 /* Static description of a status code; never NULL. */
 const char *dsattn_strerror(int code);
 

@@ -29,7 +29,7 @@ EXPORTS = (
     "dsattn_plan", "dsattn_plan_destroy", "dsattn_plan_ctx_max", "dsattn_plan_ctx_indices",
     "dsattn_plan_launch_info", "dsattn_gather_context", "dsattn_forward", "dsattn_forward_ctx",
     "dsattn_copy_probe", "dsattn_strerror", "dsattn_last_error", "dsattn_groupnorm_workspace",
-    "dsattn_groupnorm",
+    "dsattn_groupnorm", "dsattn_temporal_conv_info", "dsattn_temporal_conv",
 )
 
 
@@ -49,6 +49,26 @@ class DsattnGnDesc(ctypes.Structure):
         ("channels", ctypes.c_int32), ("groups", ctypes.c_int32), ("io_dtype", ctypes.c_int32),
         ("eps", ctypes.c_float),
     ]
+
+
+class DsattnConvDesc(ctypes.Structure):
+    _fields_ = [
+        ("clip_len", ctypes.c_int32), ("n_clips", ctypes.c_int32), ("spatial", ctypes.c_int32),
+        ("c_in", ctypes.c_int32), ("c_out", ctypes.c_int32), ("reach", ctypes.c_int32),
+        ("io_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32), ("flags", ctypes.c_uint32),
+    ]
+
+
+class DsattnConvInfo(ctypes.Structure):
+    _fields_ = [
+        ("kernel", ctypes.c_int32), ("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32),
+        ("tile_k", ctypes.c_int32), ("n_blocks", ctypes.c_int32), ("block_threads", ctypes.c_int32),
+        ("lds_bytes", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("useful_flops", ctypes.c_int64), ("algorithmic_bytes", ctypes.c_int64),
+    ]
+
+    def as_dict(self):
+        return {name: int(getattr(self, name)) for name, _ in self._fields_ if name != "reserved"}
 
 
 class DsattnLaunchInfo(ctypes.Structure):
@@ -109,6 +129,11 @@ def load():
     lib.dsattn_groupnorm_workspace.restype = ctypes.c_int
     lib.dsattn_groupnorm_workspace.argtypes = [ctypes.POINTER(DsattnGnDesc),
                                                ctypes.POINTER(ctypes.c_size_t)]
+    lib.dsattn_temporal_conv_info.restype = ctypes.c_int
+    lib.dsattn_temporal_conv_info.argtypes = [ctypes.POINTER(DsattnConvDesc),
+                                              ctypes.POINTER(DsattnConvInfo)]
+    lib.dsattn_temporal_conv.restype = ctypes.c_int
+    lib.dsattn_temporal_conv.argtypes = [ctypes.POINTER(DsattnConvDesc), vp, vp, vp, vp, vp]
     lib.dsattn_groupnorm.restype = ctypes.c_int
     lib.dsattn_groupnorm.argtypes = [ctypes.POINTER(DsattnGnDesc), vp, vp, vp, vp, vp, vp,
                                      ctypes.c_size_t, vp]
@@ -267,3 +292,21 @@ def dsattn_groupnorm(clip_len, n_clips, spatial, channels, groups, X, Y, workspa
     _check(load().dsattn_groupnorm(ctypes.byref(desc), _ptr(X), _ptr(gamma), _ptr(beta), _ptr(Y),
                                    _ptr(stats), _ptr(workspace), int(workspace_bytes),
                                    _stream(stream)), "dsattn_groupnorm")
+
+
+def dsattn_temporal_conv_info(clip_len, n_clips, spatial, c_in, c_out, reach,
+                              io_dtype=DSATTN_BF16, out_dtype=None, flags=0) -> dict:
+    desc = DsattnConvDesc(clip_len, n_clips, spatial, c_in, c_out, reach, io_dtype,
+                          io_dtype if out_dtype is None else out_dtype, flags)
+    info = DsattnConvInfo()
+    _check(load().dsattn_temporal_conv_info(ctypes.byref(desc), ctypes.byref(info)),
+           "dsattn_temporal_conv_info")
+    return info.as_dict()
+
+
+def dsattn_temporal_conv(clip_len, n_clips, spatial, c_in, c_out, reach, X, W, Y, bias=None,
+                         io_dtype=DSATTN_BF16, out_dtype=None, flags=0, stream=None):
+    desc = DsattnConvDesc(clip_len, n_clips, spatial, c_in, c_out, reach, io_dtype,
+                          io_dtype if out_dtype is None else out_dtype, flags)
+    _check(load().dsattn_temporal_conv(ctypes.byref(desc), _ptr(X), _ptr(W), _ptr(bias), _ptr(Y),
+                                       _stream(stream)), "dsattn_temporal_conv")

@@ -15,7 +15,7 @@ LIB = os.path.join(HERE, "libdsattn.so")
 
 SOURCES = ["mfma_d40.hip", "mfma_d32.hip", "mfma_d96.hip", "mfma_d80.hip", "mfma_d64.hip",
            "mfma_d160.hip", "mfma_d128.hip", "dsattn_api.hip", "kernels_generic.hip",
-           "kernel_mfma.hip", "groupnorm.hip"]
+           "kernel_mfma.hip", "groupnorm.hip", "tconv.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -139,3 +139,15 @@ def to_f64_numpy(t, heads: int):
     x = t.detach().to("cpu").to(torch.float64).numpy()
     F, P, C = x.shape
     return x.reshape(F, P, heads, C // heads)
+
+
+def make_conv_weights(taps: int, c_out: int, c_in: int, seed: int, dtype: str, device="cpu"):
+    """Weights [taps, c_out, c_in] ~ N(0, 1 / (taps * c_in)) (unit-variance outputs for unit-variance
+    inputs) rounded to `dtype`, and an fp32 bias [c_out] ~ 0.1 * N(0, 1)."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed))
+    w = torch.randn((taps, c_out, c_in), generator=gen, device=device, dtype=torch.float32)
+    w = (w / float(taps * c_in) ** 0.5).to(torch_dtype(dtype))
+    b = 0.1 * torch.randn((c_out,), generator=gen, device=device, dtype=torch.float32)
+    return w, b

@@ -1,0 +1,202 @@
+"""Clip-parallel temporal convolution (Section 4.2, "Convolution module"): boundary checks and the
+tile chooser on the CPU, parity of the HIP kernels against the oracle on the GPU."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import parity_util as U
+from oracle import oracle
+from paper_2406_16260_amd import binding as B
+from paper_2406_16260_amd import synth
+
+DEV = "cuda:0"
+
+# fp32 accumulation of up to a few thousand bf16 x bf16 products (exact in fp32) into outputs of
+# unit variance: observed errors are ~1e-5; the bar leaves a factor of ten
+TOL_ACC = 1e-4
+
+
+# ---------------------------------------------------------------- CPU: validation and tile choice
+
+def raw_desc(**kw):
+    d = dict(clip_len=16, n_clips=3, spatial=5, c_in=64, c_out=64, reach=1, io_dtype=B.DSATTN_BF16,
+             out_dtype=B.DSATTN_BF16, flags=0)
+    d.update(kw)
+    return B.DsattnConvDesc(**d)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(clip_len=0), dict(n_clips=0), dict(spatial=0), dict(c_in=0), dict(c_out=0),
+    dict(reach=-1), dict(reach=17), dict(io_dtype=2), dict(out_dtype=7), dict(flags=4),
+    dict(io_dtype=B.DSATTN_F32, out_dtype=B.DSATTN_BF16),
+])
+def test_conv_rejects_bad_descriptors(kw):
+    lib = B.load()
+    d = raw_desc(**kw)
+    info = B.DsattnConvInfo()
+    assert lib.dsattn_temporal_conv_info(ctypes.byref(d), ctypes.byref(info)) == B.DSATTN_EINVAL
+    assert lib.dsattn_temporal_conv(ctypes.byref(d), 0x1000, 0x2000, None, 0x100000, None) == \
+        B.DSATTN_EINVAL
+
+
+def test_conv_argument_checks_before_launch():
+    lib = B.load()
+    d = raw_desc()
+    info = B.DsattnConvInfo()
+    assert lib.dsattn_temporal_conv_info(None, ctypes.byref(info)) == B.DSATTN_EINVAL
+    assert lib.dsattn_temporal_conv_info(ctypes.byref(d), None) == B.DSATTN_EINVAL
+    assert lib.dsattn_temporal_conv(ctypes.byref(d), None, 0x2000, None, 0x100000, None) == B.DSATTN_EINVAL
+    assert lib.dsattn_temporal_conv(ctypes.byref(d), 0x1000, None, None, 0x100000, None) == B.DSATTN_EINVAL
+    assert lib.dsattn_temporal_conv(ctypes.byref(d), 0x1000, 0x2000, None, None, None) == B.DSATTN_EINVAL
+    assert lib.dsattn_temporal_conv(ctypes.byref(d), 0x1008, 0x2000, None, 0x100000, None) == B.DSATTN_EINVAL
+    assert "aligned" in B.dsattn_last_error()
+    assert lib.dsattn_temporal_conv(ctypes.byref(d), 0x1000, 0x2000, 0x3002, 0x100000, None) == B.DSATTN_EINVAL
+    # X is 48 * 5 * 64 * 2 = 30,720 bytes: an output starting inside it is refused
+    assert lib.dsattn_temporal_conv(ctypes.byref(d), 0x10000, 0x2000, None, 0x10000 + 30704, None) == \
+        B.DSATTN_EINVAL
+    assert "overlaps" in B.dsattn_last_error()
+    assert lib.dsattn_temporal_conv(ctypes.byref(d), 0x10000, 0x2000, None, 0x10000, None) == B.DSATTN_EINVAL
+
+
+def test_conv_info_tiles_and_counts():
+    # the headline level's shape: 2,304 frames x 160 positions, 1,280 -> 1,280 channels, 3 taps
+    i = B.dsattn_temporal_conv_info(16, 144, 160, 1280, 1280, 1)
+    M = 2304 * 160
+    assert i["kernel"] == 1 and i["block_threads"] == 256 and i["tile_k"] == 64
+    assert 1280 % i["tile_n"] == 0 and M % i["tile_m"] == 0          # no padded area at this shape
+    tiles = (M // i["tile_m"]) * (1280 // i["tile_n"])
+    assert tiles <= i["n_blocks"] < tiles + 8 and i["n_blocks"] % 8 == 0
+    assert i["lds_bytes"] == 2 * (i["tile_m"] + i["tile_n"]) * 144 <= 160 * 1024
+    # frames 0 and F-1 each lose one tap
+    assert i["useful_flops"] == 2 * (3 * 2304 - 2) * 160 * 1280 * 1280
+    assert i["algorithmic_bytes"] == 2 * (M * 1280 * 2) + 3 * 1280 * 1280 * 2
+    # 320 and 640 output channels take the 320-wide tile (no wasted columns)
+    assert B.dsattn_temporal_conv_info(16, 4, 2560, 320, 320, 1)["tile_n"] == 320
+    assert B.dsattn_temporal_conv_info(16, 24, 640, 640, 640, 1)["tile_n"] == 320
+    assert B.dsattn_temporal_conv_info(16, 24, 640, 640, 512, 1)["tile_n"] == 256
+    # no taps beyond the centre: one tap, nothing lost at the ends
+    assert B.dsattn_temporal_conv_info(4, 2, 3, 8, 8, 0)["useful_flops"] == 2 * 8 * 3 * 8 * 8
+    assert B.dsattn_temporal_conv_info(4, 2, 3, 8, 8, 2)["useful_flops"] == 2 * (5 * 8 - 6) * 3 * 8 * 8
+    # fp32 tensors, channel counts that are not whole 16-byte lanes, and the flag: vector kernel
+    assert B.dsattn_temporal_conv_info(16, 4, 5, 64, 64, 1, io_dtype=B.DSATTN_F32)["kernel"] == 0
+    assert B.dsattn_temporal_conv_info(16, 4, 5, 36, 64, 1)["kernel"] == 0
+    assert B.dsattn_temporal_conv_info(16, 4, 5, 64, 64, 1,
+                                       flags=B.DSATTN_FLAG_FORCE_GENERIC)["kernel"] == 0
+    assert B.dsattn_temporal_conv_info(16, 4, 5, 40, 7, 1)["kernel"] == 1
+
+
+# ---------------------------------------------------------------- GPU: parity
+
+def announce(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+def run_conv(x, w, b, clip_len, n_clips, out_dtype, flags=0):
+    F, P, c_in = x.shape
+    taps, c_out, _ = w.shape
+    io = "f32" if x.dtype == torch.float32 else "bf16"
+    y = torch.full((F, P, c_out), float("nan"), dtype=synth.torch_dtype(out_dtype), device=x.device)
+    B.dsattn_temporal_conv(clip_len, n_clips, P, c_in, c_out, taps // 2, x, w, y, bias=b,
+                           io_dtype=U.dt_code(io), out_dtype=U.dt_code(out_dtype), flags=flags)
+    torch.cuda.synchronize()
+    return y
+
+
+def check_conv(y, ref, out_dtype, what):
+    got = y.to("cpu").to(torch.float64).numpy()
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    err = np.abs(got - ref)
+    scale = np.maximum(1.0, np.abs(ref))
+    if out_dtype == "f32":
+        allow = TOL_ACC * scale
+    else:  # the result within TOL_ACC, then one rounding to bf16
+        allow = TOL_ACC * scale + U.bf16_half_ulp(np.maximum(np.abs(ref), np.abs(got)))
+    bad = err > allow
+    assert not bad.any(), (f"{what}: {int(bad.sum())} elements beyond the bar, max-abs {err.max():.3e} "
+                           f"at |ref| {np.abs(ref[bad]).max():.3f}")
+    return float(err.max())
+
+
+def conv_case(clip_len, n_clips, P, c_in, c_out, n, dtype="bf16", out_dtypes=("f32", "bf16"),
+              bias=True, gen="correlated", seed=70, flags=0, expect_kernel=None):
+    F = clip_len * n_clips
+    x = synth.make_tensor(F, P, c_in, seed, gen, dtype).to(DEV)
+    w, b = synth.make_conv_weights(2 * n + 1, c_out, c_in, seed + 1, dtype)
+    w, b = w.to(DEV), (b.to(DEV) if bias else None)
+    ref = oracle.temporal_conv(x.to("cpu").to(torch.float64).numpy(),
+                               w.to("cpu").to(torch.float64).numpy(), clip_len, n_clips,
+                               bias=None if b is None else b.to("cpu").to(torch.float64).numpy())
+    info = B.dsattn_temporal_conv_info(clip_len, n_clips, P, c_in, c_out, n,
+                                       io_dtype=U.dt_code(dtype), flags=flags)
+    if expect_kernel is not None:
+        assert info["kernel"] == expect_kernel, info
+    for od in out_dtypes:
+        if dtype == "f32" and od != "f32":
+            continue
+        announce(f"conv Fc={clip_len} N={n_clips} P={P} cin={c_in} cout={c_out} n={n} {dtype}->{od} "
+                 f"bias={bias} kernel={info['kernel']} tile={info['tile_m']}x{info['tile_n']}")
+        y = run_conv(x, w, b, clip_len, n_clips, od, flags=flags)
+        check_conv(y, ref, od, f"conv {c_in}->{c_out} n={n} {od}")
+    return info
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("shape", [
+    # clip_len, n_clips, P, c_in, c_out, n
+    (16, 3, 5, 64, 64, 1),          # one partly filled tile, one step per tap
+    (16, 4, 40, 128, 320, 1),       # 2,560 rows: ten row tiles of 256 or 13.3 of 192; 320-wide tile
+    (16, 3, 7, 320, 256, 1),        # row tail (336 rows), 5 steps per tap
+    (8, 5, 9, 72, 200, 2),          # c_in not a multiple of 64 (zero-filled chunks), column tail, 5 taps
+    (16, 2, 3, 1280, 1280, 1),      # the headline level's channels on a short video
+    (4, 6, 33, 40, 7, 4),           # reach = clip length, 7 output channels
+    (16, 2, 160, 64, 640, 0),       # a single tap: a plain matrix product
+    (2, 40, 50, 96, 96, 1),         # many short clips, frames cross tile borders at every offset
+])
+def test_conv_mfma_matches_oracle(shape):
+    conv_case(*shape, expect_kernel=1)
+
+
+@pytest.mark.gpu
+def test_conv_mfma_without_bias_and_iid_inputs():
+    conv_case(16, 3, 10, 192, 128, 1, bias=False, gen="iid", expect_kernel=1)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("shape,dtype", [
+    ((4, 3, 5, 6, 7, 1), "f32"), ((16, 2, 3, 36, 20, 1), "bf16"), ((3, 5, 4, 8, 8, 3), "f32"),
+    ((16, 2, 4, 64, 64, 1), "bf16"),
+])
+def test_conv_generic_matches_oracle(shape, dtype):
+    conv_case(*shape, dtype=dtype, flags=B.DSATTN_FLAG_FORCE_GENERIC, expect_kernel=0)
+
+
+@pytest.mark.gpu
+def test_conv_kernels_agree_and_are_deterministic():
+    F, P, c = 48, 12, 256
+    x = synth.make_tensor(F, P, c, 5, "iid", "bf16").to(DEV)
+    w, b = (t.to(DEV) for t in synth.make_conv_weights(3, c, c, 6, "bf16"))
+    y1 = run_conv(x, w, b, 16, 3, "f32")
+    y2 = run_conv(x, w, b, 16, 3, "f32")
+    assert torch.equal(y1, y2)
+    yg = run_conv(x, w, b, 16, 3, "f32", flags=B.DSATTN_FLAG_FORCE_GENERIC)
+    assert float((y1 - yg).abs().max()) <= TOL_ACC
+    # the clip partition cannot matter
+    y3 = run_conv(x, w, b, 4, 12, "f32")
+    assert torch.equal(y1, y3)
+
+
+@pytest.mark.gpu
+def test_conv_on_side_stream():
+    F, P, c = 32, 6, 128
+    x = synth.make_tensor(F, P, c, 9, "iid", "bf16").to(DEV)
+    w, b = (t.to(DEV) for t in synth.make_conv_weights(3, c, c, 10, "bf16"))
+    ref = run_conv(x, w, b, 16, 2, "bf16")
+    s = torch.cuda.Stream()
+    y = torch.zeros_like(ref)
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        B.dsattn_temporal_conv(16, 2, P, c, c, 1, x, w, y, bias=b, stream=s)
+    s.synchronize()
+    assert torch.equal(y, ref)
