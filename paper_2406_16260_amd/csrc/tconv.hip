@@ -32,10 +32,12 @@ namespace dsattn {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBK = 64;       // contraction depth per step (bf16 elements)
-constexpr int kRS = 144;      // LDS row stride in bytes: 128 B of data + 16 B of padding
+constexpr int kRow = 128;     // bytes of one LDS row: the 64 channels of a step, unpadded
 constexpr int kXcds = 8;
 
 struct ConvArgs {
@@ -48,15 +50,16 @@ struct ConvArgs {
     int32_t KS;                // steps in all = taps * KC
     int32_t tiles_n, tiles;    // column tiles, all tiles
     int32_t per_xcd;           // ceil(tiles / 8)
+    int32_t w_bytes;           // taps * c_out * c_in * 2
 };
 
 template <int MI, int NJ, bool OUT_F32>
 __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
 {
     constexpr int BM = 64 * MI, BN = 64 * NJ;
-    constexpr int LA = BM / 32, LB = BN / 32;  // 16-byte loads per thread and step for X and W
-    constexpr int ABYTES = BM * kRS, BBYTES = BN * kRS;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int GA = BM / 32, GB = BN / 32;  // 8-row groups (one load instruction) per wavefront
+    constexpr int ABYTES = BM * kRow, BUF = (BM + BN) * kRow;
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     // workgroup -> tile: XCD x (= blockIdx % 8) walks tiles [x * per_xcd, (x + 1) * per_xcd)
     const int tile = (int)(blockIdx.x % kXcds) * a.per_xcd + (int)(blockIdx.x / kXcds);
@@ -65,46 +68,70 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
     const int64_t m0 = (int64_t)mt * BM;
     const int n0 = nt * BN;
 
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wv >> 1, wn = wv & 1;
-    const int lrow = tid >> 3;  // row (mod 32) this thread loads
-    const int lch = tid & 7;    // 16-byte chunk of the 128-byte step row
 
-    const __bf16 *X = (const __bf16 *)a.X;
-    const __bf16 *W = (const __bf16 *)a.W;
+    // Global -> LDS without passing through registers: one buffer_load ... lds instruction moves
+    // 8 rows x 128 B; lane l lands at LDS position l (16 B each) of the instruction's 1 KB block,
+    // i.e. row l / 8, position l % 8, and fetches chunk (l % 8) ^ (l / 8) of that row: position s
+    // of row r holds chunk s ^ (r % 8), which spreads a column of chunks over all banks.
+    // Out-of-range lanes (rows outside the video, channels past c_in, columns past c_out) get
+    // an offset beyond the buffer's extent, for which the hardware delivers zeros.
+    const int lr = lane >> 3;
+    const int lc = (lane & 7) ^ lr;
+    const int64_t rb = max((int64_t)0, m0 - (int64_t)a.n * a.P);  // first row the tile can touch
+    const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)((const __bf16 *)a.X + rb * a.Cin), 0,
+        (int)min((a.M - rb) * a.Cin * 2, (int64_t)0x7fffffff), 0x00020000);
+    const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)a.W, 0, (int)a.w_bytes, 0x00020000);
+    constexpr uint32_t kOob = 0xfffffff0u;
+    const int rowbytes = a.Cin * 2;
+    const int xrow0 = wv * (8 * GA) + lr;  // this lane's first X row within the tile
+    const int wrow0 = wv * (8 * GB) + lr;  // this lane's first W row within the tile
 
-    uint4 ra[LA], rb[LB];
-    // step ks = tap * KC + channel block: rows of X at the tap's frame offset, rows of W_tap
-    auto gload = [&](int ks) __attribute__((always_inline)) {
+    // per-step load state, set by step_setup(), used by issue_one()
+    int ld_lo = 0, ld_xstep = 0, ld_wstep = 0;
+    uint32_t ld_xspan = 0, ld_wspan = 0;
+    unsigned char *ld_as = smem, *ld_bs = smem;
+    // `on` = false turns every lane of the step's loads into an out-of-range one (after the
+    // last step: no traffic, and no branch inside the multiply schedule)
+    auto step_setup = [&](int ks, int buf, bool on) __attribute__((always_inline)) {
         const int t = ks / a.KC, kc = ks - t * a.KC;
-        const int ci = kc * kBK + lch * 8;
-        const bool cok = ci < a.Cin;  // c_in is a multiple of 8: a chunk is all in or all out
-        const int64_t mrow = m0 + (int64_t)(t - a.n) * a.P + lrow;
-#pragma unroll
-        for (int j = 0; j < LA; ++j) {
-            const int64_t m = mrow + 32 * j;
-            uint4 x = make_uint4(0, 0, 0, 0);
-            if (cok && m >= 0 && m < a.M) x = *(const uint4 *)(X + m * a.Cin + ci);
-            ra[j] = x;
-        }
-        const __bf16 *Wt = W + (int64_t)t * a.Cout * a.Cin;
-#pragma unroll
-        for (int j = 0; j < LB; ++j) {
-            const int co = n0 + lrow + 32 * j;
-            uint4 x = make_uint4(0, 0, 0, 0);
-            if (cok && co < a.Cout) x = *(const uint4 *)(Wt + (int64_t)co * a.Cin + ci);
-            rb[j] = x;
-        }
+        const bool cok = on && kc * kBK + lc * 8 < a.Cin;  // c_in % 8 == 0: a chunk is all in or out
+        const int64_t mshift = m0 + (int64_t)(t - a.n) * a.P;  // video row of tile row 0 at this tap
+        // tile rows [lo, lo + span) are inside the video at this tap (none for a lane whose
+        // channels are past c_in); branch-free so that the loads stay one straight run
+        const int hi = (int)min((int64_t)0x40000000, a.M - mshift);
+        ld_lo = (int)max((int64_t)-0x40000000, -mshift);
+        ld_xspan = cok ? (uint32_t)max(hi - ld_lo, 0) : 0u;
+        ld_wspan = cok ? (uint32_t)max(a.Cout - n0, 0) : 0u;
+        ld_xstep = (int)(mshift - rb) * rowbytes + kc * (kBK * 2) + lc * 16;
+        ld_wstep = (t * a.Cout + n0) * rowbytes + kc * (kBK * 2) + lc * 16;
+        ld_as = smem + buf * BUF + wv * (GA * 1024);
+        ld_bs = smem + buf * BUF + ABYTES + wv * (GB * 1024);
     };
-    auto lstore = [&](int buf) __attribute__((always_inline)) {
-        unsigned char *As = smem + buf * (ABYTES + BBYTES);
-        unsigned char *Bs = As + ABYTES;
-#pragma unroll
-        for (int j = 0; j < LA; ++j) *(uint4 *)(As + (lrow + 32 * j) * kRS + lch * 16) = ra[j];
-#pragma unroll
-        for (int j = 0; j < LB; ++j) *(uint4 *)(Bs + (lrow + 32 * j) * kRS + lch * 16) = rb[j];
+    constexpr int NL = GA + GB;  // loads per wavefront and step
+    auto issue_one = [&](int l) __attribute__((always_inline)) {
+        if (l < GA) {
+            const int r = xrow0 + 8 * l;
+            const uint32_t off = (uint32_t)(r * rowbytes + ld_xstep);
+            const uint32_t voff = (uint32_t)(r - ld_lo) < ld_xspan ? off : kOob;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                xres, (__attribute__((address_space(3))) void *)(ld_as + l * 1024), 16, voff, 0, 0, 0);
+        } else {
+            const int r = wrow0 + 8 * (l - GA);
+            const uint32_t off = (uint32_t)(r * rowbytes + ld_wstep);
+            const uint32_t voff = (uint32_t)r < ld_wspan ? off : kOob;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                wres, (__attribute__((address_space(3))) void *)(ld_bs + (l - GA) * 1024), 16, voff, 0,
+                0, 0);
+        }
     };
 
+    // acc[i][j] is the 32 x 32 block (32 output channels) x (32 rows of Y): W rows are the A
+    // operand, X rows the B operand, so that a lane ends up with 4 consecutive channels of one row
     f32x16 acc[MI][NJ];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
@@ -113,62 +140,180 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    gload(0);
-    lstore(0);
-    __syncthreads();
+    // operand addresses: MFMA row/column lane & 31 (row % 8 = lane % 8), contraction group
+    // lane >> 5; step kk needs chunk 2 kk + (lane >> 5), which sits at position chunk ^ (row % 8)
+    int koff[kBK / 16];
+#pragma unroll
+    for (int kk = 0; kk < kBK / 16; ++kk) koff[kk] = (((2 * kk) | (lane >> 5)) ^ (lane & 7)) * 16;
+    const int abase = (wm * 32 * MI + (lane & 31)) * kRow;
+    const int bbase = ABYTES + (wn * 32 * NJ + (lane & 31)) * kRow;
 
-    // operand addresses: MFMA row/column lane & 31, contraction group lane >> 5 (8 bf16 each)
-    const int arow = (wm * 32 * MI + (lane & 31)) * kRS + (lane >> 5) * 16;
-    const int brow = (wn * 32 * NJ + (lane & 31)) * kRS + (lane >> 5) * 16;
+    // Operand fragments of contraction sub-step kk of a buffer, double buffered in registers.
+    // The loop below is scheduled by hand (sched_barrier pins the order): with one wavefront
+    // per SIMD nothing else hides latency, so every sub-step's multiplies are interleaved with
+    // the LDS reads of the next sub-step's fragments (also across the barrier between steps)
+    // and, in the first half of a step, with the issue of the next step's global loads (a
+    // wavefront that issues them back to back sits in the memory pipeline's queue meanwhile).
+    bf16x8 af[2][MI], bfr[2][NJ];
+    constexpr int NR = MI + NJ, NM = MI * NJ;
+    constexpr int NKK = kBK / 16;
+    static_assert(NKK % 2 == 0, "fragment slots alternate and must line up across steps");
+    constexpr int NLK = (NL + 1) / 2;  // global loads issued in each of the first two sub-steps
+    auto read_frag = [&](const unsigned char *base, int kk, int slot, int r)
+                         __attribute__((always_inline)) {
+        if (r < MI)
+            af[slot][r] = *(const bf16x8 *)(base + abase + r * (32 * kRow) + koff[kk]);
+        else
+            bfr[slot][r - MI] = *(const bf16x8 *)(base + bbase + (r - MI) * (32 * kRow) + koff[kk]);
+    };
+    // multiplies [mlo, mhi) of the sub-step whose fragments are in `slot`; read r of the next
+    // fragments (sub-step kk of `base`) goes before multiply mlo + floor(r (mhi - mlo) / NR) when
+    // do_reads; global load ld0 + q goes before multiply floor(q NM / NLK) when ld0 >= 0
+    auto mma_range = [&](int slot, int mlo, int mhi, bool do_reads, const unsigned char *base, int kk,
+                         int ld0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+            if (m < mlo || m >= mhi) continue;
+#pragma unroll
+            for (int q = 0; q < NLK; ++q)
+                if (ld0 >= 0 && ld0 + q < NL && (q * NM) / NLK == m) {
+                    issue_one(ld0 + q);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+                if (do_reads && mlo + (r * (mhi - mlo)) / NR == m) {
+                    read_frag(base, kk, slot ^ 1, r);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            const int i = m / NJ, j = m - i * NJ;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[slot][j], af[slot][i], acc[i][j],
+                                                                0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    step_setup(0, 0, true);
+#pragma unroll
+    for (int l = 0; l < NL; ++l) issue_one(l);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < NR; ++r) read_frag(smem, 0, 0, r);
 
     for (int ks = 0; ks < a.KS; ++ks) {
         const int cur = ks & 1;
-        const bool more = ks + 1 < a.KS;
-        if (more) gload(ks + 1);
-        const unsigned char *As = smem + cur * (ABYTES + BBYTES);
-        const unsigned char *Bs = As + ABYTES;
-#pragma unroll
-        for (int kk = 0; kk < kBK / 16; ++kk) {
-            bf16x8 af[MI], bfr[NJ];
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-                af[i] = *(const bf16x8 *)(As + arow + i * 32 * kRS + kk * 32);
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-                bfr[j] = *(const bf16x8 *)(Bs + brow + j * 32 * kRS + kk * 32);
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NJ; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0,
-                                                                        0, 0);
-        }
         // the other buffer was last read in step ks - 1, which every wavefront has left
-        if (more) lstore(cur ^ 1);
+        step_setup(ks + 1, cur ^ 1, ks + 1 < a.KS);
+        __builtin_amdgcn_sched_barrier(0);
+        const unsigned char *bufc = smem + cur * BUF;
+        const unsigned char *bufn = smem + (cur ^ 1) * BUF;
+#pragma unroll
+        for (int kk = 0; kk + 1 < NKK; ++kk)
+            mma_range(kk & 1, 0, NM, true, bufc, kk + 1, kk < 2 ? kk * NLK : -1);
+        // last sub-step: half of its multiplies, then the barrier (this wavefront's loads have
+        // landed; after the barrier everybody's have), then the first fragments of the next
+        // step interleaved with the other half.  After the last step those fragments are never
+        // used: the reads stay in bounds, and keeping them unconditional keeps the multiplies
+        // out of divergent control flow.
+        mma_range((NKK - 1) & 1, 0, NM / 2, false, bufc, 0, -1);
+        __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        mma_range(((NKK - 1) & 1), NM / 2, NM, true, bufn, 0, -1);
     }
 
-    // epilogue: accumulator element e of lane l is row 8 (e / 4) + 4 (l / 32) + e % 4, column
-    // l % 32 of its 32 x 32 block
+    // epilogue: accumulator element e of lane l is output channel 8 (e / 4) + 4 (l / 32) + e % 4
+    // and row l % 32 of its block: four consecutive channels per lane and e / 4.
+    // The bias of the wavefront's 32 NJ channels goes through LDS once (zeros where there is no
+    // bias or no channel), so that the stores below depend on no global load.
+    constexpr int SROW = 64 * NJ + 8;
+    constexpr int STAGE = 32 * MI * SROW;
+    constexpr int BIAS_OFF = (2 * BUF > 4 * STAGE) ? 2 * BUF : 4 * STAGE;
+    const int cbase = n0 + wn * 32 * NJ;     // first channel of this wavefront's part
+    const int64_t mrow0 = m0 + wm * 32 * MI;  // first row of this wavefront's part
+    float *bl = (float *)(smem + BIAS_OFF) + wv * (32 * NJ);
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-        const int co = n0 + wn * 32 * NJ + 32 * j + (lane & 31);
-        if (co >= a.Cout) continue;
-        const float b = a.bias ? a.bias[co] : 0.f;
+    for (int c = lane; c < 32 * NJ; c += 64)
+        bl[c] = (a.bias && cbase + c < a.Cout) ? a.bias[cbase + c] : 0.f;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    if constexpr (!OUT_F32) {
+        if ((a.Cout & 7) == 0) {
+            // bf16 rows made of whole 16-byte pieces: the wavefront's (32 MI) x (32 NJ) part goes
+            // through its own LDS region (the loop's last barrier has retired every load and
+            // every read of the operand buffers that matters) and leaves as full rows: each
+            // store instruction writes 64 NJ contiguous bytes per row.  Rows are padded by 8
+            // bytes so that the 8-byte writes of 32 consecutive rows spread over the banks.
+            constexpr int CPR = 4 * NJ;  // 16-byte pieces per row
+            unsigned char *stg = smem + wv * STAGE;
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int64_t m = m0 + wm * 32 * MI + 32 * i + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                if (m < a.M) {
-                    const float y = acc[i][j][e] + b;
-                    if constexpr (OUT_F32)
-                        ((float *)a.Y)[m * a.Cout + co] = y;
-                    else
-                        ((__bf16 *)a.Y)[m * a.Cout + co] = (__bf16)y;
+                for (int g = 0; g < 4; ++g) {
+                    const int cl = 32 * j + 8 * g + 4 * (lane >> 5);  // channel within the part
+                    const f32x4 b = *(const f32x4 *)(bl + cl);
+#pragma unroll
+                    for (int i = 0; i < MI; ++i) {
+                        bf16x4 yb;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) yb[e] = (__bf16)(acc[i][j][4 * g + e] + b[e]);
+                        *(bf16x4 *)(stg + (32 * i + (lane & 31)) * SROW + cl * 2) = yb;
+                    }
+                }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int it = 0; it < (32 * MI * CPR + 63) / 64; ++it) {
+                const int q = lane + 64 * it;
+                const int row = q / CPR, pc = q - row * CPR;
+                if (q < 32 * MI * CPR && mrow0 + row < a.M && cbase + pc * 8 < a.Cout) {
+                    const uint2 lo = *(const uint2 *)(stg + row * SROW + pc * 16);
+                    const uint2 hi = *(const uint2 *)(stg + row * SROW + pc * 16 + 8);
+                    *(uint4 *)((__bf16 *)a.Y + (mrow0 + row) * a.Cout + cbase + pc * 8) =
+                        make_uint4(lo.x, lo.y, hi.x, hi.y);
                 }
             }
+            return;
+        }
     }
+    // fp32 output, or bf16 rows that are not whole 16-byte pieces: straight from the registers
+    const bool vec_ok = (a.Cout & 3) == 0;  // 8-byte (bf16) / 16-byte (fp32) stores stay aligned
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int cl = 32 * j + 8 * g + 4 * (lane >> 5);
+            const int co = cbase + cl;
+            const f32x4 b = *(const f32x4 *)(bl + cl);
+#pragma unroll
+            for (int i = 0; i < MI; ++i) {
+                const int64_t m = mrow0 + 32 * i + (lane & 31);
+                if (m >= a.M || co >= a.Cout) continue;
+                const f32x4 y = {acc[i][j][4 * g] + b[0], acc[i][j][4 * g + 1] + b[1],
+                                 acc[i][j][4 * g + 2] + b[2], acc[i][j][4 * g + 3] + b[3]};
+                if (vec_ok) {  // c_out % 4 == 0 and co % 4 == 0: all four channels exist
+                    if constexpr (OUT_F32) {
+                        *(f32x4 *)((float *)a.Y + m * a.Cout + co) = y;
+                    } else {
+                        bf16x4 yb;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) yb[e] = (__bf16)y[e];
+                        *(bf16x4 *)((__bf16 *)a.Y + m * a.Cout + co) = yb;
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (co + e < a.Cout) {
+                            if constexpr (OUT_F32)
+                                ((float *)a.Y)[m * a.Cout + co + e] = y[e];
+                            else
+                                ((__bf16 *)a.Y)[m * a.Cout + co + e] = (__bf16)y[e];
+                        }
+                }
+            }
+        }
 }
 
 // Plain vector kernel for every other case (fp32 tensors, c_in not a multiple of 8): one
@@ -229,6 +374,10 @@ const ConvVariant *conv_pick(const dsattn_conv_desc &d, int64_t M)
 {
     if (d.io_dtype != DSATTN_BF16 || d.c_in % 8 != 0 || (d.flags & DSATTN_FLAG_FORCE_GENERIC))
         return nullptr;
+    // the kernel addresses W, and the rows of X one tile can touch, with 32-bit byte offsets
+    const int64_t taps = 2 * (int64_t)d.reach + 1;
+    if (taps * d.c_out * d.c_in * 2 >= ((int64_t)1 << 31)) return nullptr;
+    if ((320 + 2 * (int64_t)d.reach * d.spatial) * d.c_in * 2 >= ((int64_t)1 << 31)) return nullptr;
     const ConvVariant *best = nullptr;
     double best_cost = 0;
     for (const ConvVariant &v : kConvVariants) {
@@ -244,7 +393,13 @@ const ConvVariant *conv_pick(const dsattn_conv_desc &d, int64_t M)
     return best;
 }
 
-int conv_lds_bytes(const ConvVariant &v) { return 2 * (64 * v.MI + 64 * v.NJ) * kRS; }
+// two operand buffers, reused by the bf16 epilogue as four (32 MI) x (64 NJ + 8)-byte regions;
+// behind them the bias of each wavefront's 32 NJ channels
+int conv_lds_bytes(const ConvVariant &v)
+{
+    return std::max(2 * (64 * v.MI + 64 * v.NJ) * kRow, 4 * 32 * v.MI * (64 * v.NJ + 8)) +
+           4 * 32 * v.NJ * (int)sizeof(float);
+}
 
 }  // namespace
 
@@ -350,6 +505,7 @@ int dsattn_temporal_conv(const dsattn_conv_desc *desc, const void *X, const void
             a.tiles_n = (int32_t)((d.c_out + bn - 1) / bn);
             a.tiles = (int32_t)(((M + bm - 1) / bm) * a.tiles_n);
             a.per_xcd = (a.tiles + kXcds - 1) / kXcds;
+            a.w_bytes = (int32_t)((2 * (int64_t)d.reach + 1) * d.c_out * d.c_in * 2);
             void *params[] = {&a};
             e = hipLaunchKernel(fn, dim3((unsigned)(a.per_xcd * kXcds)), dim3(256), params,
                                 (size_t)lds, st);
