@@ -36,8 +36,9 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kBK = 64;       // contraction depth per step (bf16 elements)
-constexpr int kRow = 128;     // bytes of one LDS row: the 64 channels of a step, unpadded
+constexpr int kBK = 64;       // contraction depth per stage (bf16 elements)
+constexpr int kRow = 128;     // bytes of one LDS row: the 64 channels of a stage = one cache line
+constexpr int kSlots = 2;     // LDS ring: one stage in use, one on its way
 constexpr int kXcds = 8;
 
 struct ConvArgs {
@@ -46,8 +47,8 @@ struct ConvArgs {
     void *Y;
     int64_t M;                 // rows = F * P
     int32_t P, Cin, Cout, n;
-    int32_t KC;                // steps per tap = ceil(c_in / 64)
-    int32_t KS;                // steps in all = taps * KC
+    int32_t KC;                // stages per tap = ceil(c_in / 64)
+    int32_t KS;                // stages in all = taps * KC
     int32_t tiles_n, tiles;    // column tiles, all tiles
     int32_t per_xcd;           // ceil(tiles / 8)
     int32_t w_bytes;           // taps * c_out * c_in * 2
@@ -58,7 +59,7 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
 {
     constexpr int BM = 64 * MI, BN = 64 * NJ;
     constexpr int GA = BM / 32, GB = BN / 32;  // 8-row groups (one load instruction) per wavefront
-    constexpr int ABYTES = BM * kRow, BUF = (BM + BN) * kRow;
+    constexpr int ABYTES = BM * kRow, BUF = (BM + BN) * kRow;  // one ring slot
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     // workgroup -> tile: XCD x (= blockIdx % 8) walks tiles [x * per_xcd, (x + 1) * per_xcd)
@@ -73,11 +74,17 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
     const int wm = wv >> 1, wn = wv & 1;
 
     // Global -> LDS without passing through registers: one buffer_load ... lds instruction moves
-    // 8 rows x 128 B; lane l lands at LDS position l (16 B each) of the instruction's 1 KB block,
-    // i.e. row l / 8, position l % 8, and fetches chunk (l % 8) ^ (l / 8) of that row: position s
-    // of row r holds chunk s ^ (r % 8), which spreads a column of chunks over all banks.
-    // Out-of-range lanes (rows outside the video, channels past c_in, columns past c_out) get
-    // an offset beyond the buffer's extent, for which the hardware delivers zeros.
+    // 8 rows x 128 B (whole cache lines: half lines cost the memory pipeline the same cycles);
+    // lane l lands at LDS position l (16 B each) of the instruction's 1 KB block, i.e. row l / 8,
+    // position l % 8, and fetches chunk (l % 8) ^ (l / 8) of that row: position s of row r holds
+    // chunk s ^ (r % 8), which spreads a column of chunks over all banks.
+    // Rows outside the video (frames before the first or after the last one) must read as
+    // zeros, and do without any test: the X buffer descriptor starts at the first row the tile
+    // can touch and ends with X, byte offsets are 32-bit, so a row before the video gives a
+    // negative offset (huge as unsigned) and a row after it an offset past the extent, and the
+    // hardware delivers zeros for both.  Channels past c_in (last block of a tap) are zeroed the
+    // same way, by replacing the lane's offset.  W rows past c_out need nothing: whatever they
+    // multiply into belongs to output channels that are never stored.
     const int lr = lane >> 3;
     const int lc = (lane & 7) ^ lr;
     const int64_t rb = max((int64_t)0, m0 - (int64_t)a.n * a.P);  // first row the tile can touch
@@ -86,48 +93,51 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
         (int)min((a.M - rb) * a.Cin * 2, (int64_t)0x7fffffff), 0x00020000);
     const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
         (void *)a.W, 0, (int)a.w_bytes, 0x00020000);
-    constexpr uint32_t kOob = 0xfffffff0u;
     const int rowbytes = a.Cin * 2;
-    const int xrow0 = wv * (8 * GA) + lr;  // this lane's first X row within the tile
-    const int wrow0 = wv * (8 * GB) + lr;  // this lane's first W row within the tile
+    constexpr uint32_t kOob = 0xfffffff0u;
+    int xoff[GA], woff[GB];  // byte offset of this lane's row and chunk within the tile's rows
+    // (the empty asm keeps each offset in a register: recomputing it inside the loop would put a
+    // multiply and several adds between the matrix instructions, per load)
+#pragma unroll
+    for (int l = 0; l < GA; ++l) {
+        xoff[l] = (wv * (8 * GA) + lr + 8 * l) * rowbytes + lc * 16;
+        asm volatile("" : "+v"(xoff[l]));
+    }
+#pragma unroll
+    for (int l = 0; l < GB; ++l) {
+        woff[l] = (wv * (8 * GB) + lr + 8 * l) * rowbytes + lc * 16;
+        asm volatile("" : "+v"(woff[l]));
+    }
 
-    // per-step load state, set by step_setup(), used by issue_one()
-    int ld_lo = 0, ld_xstep = 0, ld_wstep = 0;
-    uint32_t ld_xspan = 0, ld_wspan = 0;
+    // per-stage load state, set by stage_setup(), used by issue_one()
+    uint32_t ld_xstep = 0, ld_wstep = 0;
+    bool ld_live = false;  // this lane's channels exist (and the stage does)
     unsigned char *ld_as = smem, *ld_bs = smem;
-    // `on` = false turns every lane of the step's loads into an out-of-range one (after the
-    // last step: no traffic, and no branch inside the multiply schedule)
-    auto step_setup = [&](int ks, int buf, bool on) __attribute__((always_inline)) {
-        const int t = ks / a.KC, kc = ks - t * a.KC;
-        const bool cok = on && kc * kBK + lc * 8 < a.Cin;  // c_in % 8 == 0: a chunk is all in or out
+    // stage ks = channel block * taps + tap: the taps of one channel block follow each other,
+    // so that the X lines they share (the same rows, shifted by P per tap) are still in L2.
+    // Past the last stage every lane of the loads is an out-of-range one: no traffic, the same
+    // number of loads in flight, and no branch inside the multiply schedule.
+    auto stage_setup = [&](int ks) __attribute__((always_inline)) {
+        const int taps = 2 * a.n + 1;
+        const int kc = ks / taps, t = ks - kc * taps;
+        ld_live = ks < a.KS && kc * kBK + lc * 8 < a.Cin;  // c_in % 8 == 0: a chunk is all in or out
         const int64_t mshift = m0 + (int64_t)(t - a.n) * a.P;  // video row of tile row 0 at this tap
-        // tile rows [lo, lo + span) are inside the video at this tap (none for a lane whose
-        // channels are past c_in); branch-free so that the loads stay one straight run
-        const int hi = (int)min((int64_t)0x40000000, a.M - mshift);
-        ld_lo = (int)max((int64_t)-0x40000000, -mshift);
-        ld_xspan = cok ? (uint32_t)max(hi - ld_lo, 0) : 0u;
-        ld_wspan = cok ? (uint32_t)max(a.Cout - n0, 0) : 0u;
-        ld_xstep = (int)(mshift - rb) * rowbytes + kc * (kBK * 2) + lc * 16;
-        ld_wstep = (t * a.Cout + n0) * rowbytes + kc * (kBK * 2) + lc * 16;
-        ld_as = smem + buf * BUF + wv * (GA * 1024);
-        ld_bs = smem + buf * BUF + ABYTES + wv * (GB * 1024);
+        ld_xstep = (uint32_t)((int)(mshift - rb) * rowbytes + kc * (kBK * 2));
+        ld_wstep = (uint32_t)((t * a.Cout + n0) * rowbytes + kc * (kBK * 2));
+        const int slot = ks & (kSlots - 1);
+        ld_as = smem + slot * BUF + wv * (GA * 1024);
+        ld_bs = smem + slot * BUF + ABYTES + wv * (GB * 1024);
     };
-    constexpr int NL = GA + GB;  // loads per wavefront and step
+    constexpr int NL = GA + GB;  // loads per wavefront and stage
     auto issue_one = [&](int l) __attribute__((always_inline)) {
-        if (l < GA) {
-            const int r = xrow0 + 8 * l;
-            const uint32_t off = (uint32_t)(r * rowbytes + ld_xstep);
-            const uint32_t voff = (uint32_t)(r - ld_lo) < ld_xspan ? off : kOob;
+        if (l < GA)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                xres, (__attribute__((address_space(3))) void *)(ld_as + l * 1024), 16, voff, 0, 0, 0);
-        } else {
-            const int r = wrow0 + 8 * (l - GA);
-            const uint32_t off = (uint32_t)(r * rowbytes + ld_wstep);
-            const uint32_t voff = (uint32_t)r < ld_wspan ? off : kOob;
+                xres, (__attribute__((address_space(3))) void *)(ld_as + l * 1024), 16,
+                ld_live ? (uint32_t)xoff[l] + ld_xstep : kOob, 0, 0, 0);
+        else
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                wres, (__attribute__((address_space(3))) void *)(ld_bs + (l - GA) * 1024), 16, voff, 0,
-                0, 0);
-        }
+                wres, (__attribute__((address_space(3))) void *)(ld_bs + (l - GA) * 1024), 16,
+                ld_live ? (uint32_t)woff[l - GA] + ld_wstep : kOob, 0, 0, 0);
     };
 
     // acc[i][j] is the 32 x 32 block (32 output channels) x (32 rows of Y): W rows are the A
@@ -141,24 +151,24 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     // operand addresses: MFMA row/column lane & 31 (row % 8 = lane % 8), contraction group
-    // lane >> 5; step kk needs chunk 2 kk + (lane >> 5), which sits at position chunk ^ (row % 8)
+    // lane >> 5; sub-step kk needs chunk 2 kk + (lane >> 5), which sits at position chunk ^ (row % 8)
     int koff[kBK / 16];
 #pragma unroll
     for (int kk = 0; kk < kBK / 16; ++kk) koff[kk] = (((2 * kk) | (lane >> 5)) ^ (lane & 7)) * 16;
     const int abase = (wm * 32 * MI + (lane & 31)) * kRow;
     const int bbase = ABYTES + (wn * 32 * NJ + (lane & 31)) * kRow;
 
-    // Operand fragments of contraction sub-step kk of a buffer, double buffered in registers.
+    // Operand fragments of contraction sub-step kk of a slot, double buffered in registers.
     // The loop below is scheduled by hand (sched_barrier pins the order): with one wavefront
     // per SIMD nothing else hides latency, so every sub-step's multiplies are interleaved with
-    // the LDS reads of the next sub-step's fragments (also across the barrier between steps)
-    // and, in the first half of a step, with the issue of the next step's global loads (a
-    // wavefront that issues them back to back sits in the memory pipeline's queue meanwhile).
+    // the LDS reads of the next sub-step's fragments (also across the barrier between stages)
+    // and, in the first half of a stage, with the issue of the next stage's loads (a wavefront
+    // that issues them back to back sits in the memory pipeline's queue meanwhile).
     bf16x8 af[2][MI], bfr[2][NJ];
     constexpr int NR = MI + NJ, NM = MI * NJ;
     constexpr int NKK = kBK / 16;
-    static_assert(NKK % 2 == 0, "fragment slots alternate and must line up across steps");
-    constexpr int NLK = (NL + 1) / 2;  // global loads issued in each of the first two sub-steps
+    static_assert(NKK % 2 == 0, "fragment slots alternate and must line up across stages");
+    constexpr int NLK = NL / 2;  // loads issued in each of the first two sub-steps
     auto read_frag = [&](const unsigned char *base, int kk, int slot, int r)
                          __attribute__((always_inline)) {
         if (r < MI)
@@ -167,8 +177,8 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
             bfr[slot][r - MI] = *(const bf16x8 *)(base + bbase + (r - MI) * (32 * kRow) + koff[kk]);
     };
     // multiplies [mlo, mhi) of the sub-step whose fragments are in `slot`; read r of the next
-    // fragments (sub-step kk of `base`) goes before multiply mlo + floor(r (mhi - mlo) / NR) when
-    // do_reads; global load ld0 + q goes before multiply floor(q NM / NLK) when ld0 >= 0
+    // fragments (sub-step kk of `base`) goes before multiply mlo + floor(r (mhi - mlo) / NR)
+    // when do_reads; global load ld0 + q goes before multiply floor(q NM / NLK) when ld0 >= 0
     auto mma_range = [&](int slot, int mlo, int mhi, bool do_reads, const unsigned char *base, int kk,
                          int ld0) __attribute__((always_inline)) {
 #pragma unroll
@@ -176,7 +186,7 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
             if (m < mlo || m >= mhi) continue;
 #pragma unroll
             for (int q = 0; q < NLK; ++q)
-                if (ld0 >= 0 && ld0 + q < NL && (q * NM) / NLK == m) {
+                if (ld0 >= 0 && (q * NM) / NLK == m) {
                     issue_one(ld0 + q);
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -193,35 +203,39 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
         }
     };
 
-    step_setup(0, 0, true);
+    // prologue: stage 0 landed.  (Bare barriers: the wait before them is the only ordering
+    // needed, and a workgroup fence would add nothing.)
+    stage_setup(0);
 #pragma unroll
     for (int l = 0; l < NL; ++l) issue_one(l);
     __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int r = 0; r < NR; ++r) read_frag(smem, 0, 0, r);
 
     for (int ks = 0; ks < a.KS; ++ks) {
-        const int cur = ks & 1;
-        // the other buffer was last read in step ks - 1, which every wavefront has left
-        step_setup(ks + 1, cur ^ 1, ks + 1 < a.KS);
+        // the other slot was last read in stage ks - 1, which every wavefront has left
+        stage_setup(ks + 1);
         __builtin_amdgcn_sched_barrier(0);
-        const unsigned char *bufc = smem + cur * BUF;
-        const unsigned char *bufn = smem + (cur ^ 1) * BUF;
+        const unsigned char *bufc = smem + (ks & 1) * BUF;
+        const unsigned char *bufn = smem + ((ks + 1) & 1) * BUF;
 #pragma unroll
         for (int kk = 0; kk + 1 < NKK; ++kk)
             mma_range(kk & 1, 0, NM, true, bufc, kk + 1, kk < 2 ? kk * NLK : -1);
-        // last sub-step: half of its multiplies, then the barrier (this wavefront's loads have
-        // landed; after the barrier everybody's have), then the first fragments of the next
-        // step interleaved with the other half.  After the last step those fragments are never
-        // used: the reads stay in bounds, and keeping them unconditional keeps the multiplies
-        // out of divergent control flow.
+        // last sub-step: half of its multiplies, then the barrier (this wavefront's loads of
+        // stage ks + 1 have landed; after the barrier everybody's have), then the first
+        // fragments of the next stage interleaved with the other half.  After the last stage
+        // those fragments are never used: the reads stay in bounds, and keeping them
+        // unconditional keeps the multiplies out of divergent control flow.
         mma_range((NKK - 1) & 1, 0, NM / 2, false, bufc, 0, -1);
         __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
+        __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        mma_range(((NKK - 1) & 1), NM / 2, NM, true, bufn, 0, -1);
+        mma_range((NKK - 1) & 1, NM / 2, NM, true, bufn, 0, -1);
     }
+    // the loop's last barrier has retired every load (the last stage's were the out-of-range
+    // ones of the stage past the end, which write zeros) and every operand read that matters
 
     // epilogue: accumulator element e of lane l is output channel 8 (e / 4) + 4 (l / 32) + e % 4
     // and row l % 32 of its block: four consecutive channels per lane and e / 4.
@@ -229,7 +243,7 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
     // bias or no channel), so that the stores below depend on no global load.
     constexpr int SROW = 64 * NJ + 8;
     constexpr int STAGE = 32 * MI * SROW;
-    constexpr int BIAS_OFF = (2 * BUF > 4 * STAGE) ? 2 * BUF : 4 * STAGE;
+    constexpr int BIAS_OFF = (kSlots * BUF > 4 * STAGE) ? kSlots * BUF : 4 * STAGE;
     const int cbase = n0 + wn * 32 * NJ;     // first channel of this wavefront's part
     const int64_t mrow0 = m0 + wm * 32 * MI;  // first row of this wavefront's part
     float *bl = (float *)(smem + BIAS_OFF) + wv * (32 * NJ);
@@ -393,11 +407,11 @@ const ConvVariant *conv_pick(const dsattn_conv_desc &d, int64_t M)
     return best;
 }
 
-// two operand buffers, reused by the bf16 epilogue as four (32 MI) x (64 NJ + 8)-byte regions;
-// behind them the bias of each wavefront's 32 NJ channels
+// the ring of operand slots, reused by the bf16 epilogue as four (32 MI) x (64 NJ + 8)-byte
+// regions; behind them the bias of each wavefront's 32 NJ channels
 int conv_lds_bytes(const ConvVariant &v)
 {
-    return std::max(2 * (64 * v.MI + 64 * v.NJ) * kRow, 4 * 32 * v.MI * (64 * v.NJ + 8)) +
+    return std::max(kSlots * (64 * v.MI + 64 * v.NJ) * kRow, 4 * 32 * v.MI * (64 * v.NJ + 8)) +
            4 * 32 * v.NJ * (int)sizeof(float);
 }
 
