@@ -20,6 +20,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix-core rate
 METRIC = "dual-scope attn query-frame-positions/s at 1 GPU; % of HBM roofline"
 
 
@@ -180,6 +181,29 @@ def main():
     gn_ms = g0.elapsed_time(g1) / 5
     groupnorm = {"ms": round(gn_ms, 4), "GBps": round(4 * nbytes / gn_ms / 1e6, 1),
                  "algorithmic_bytes": 4 * nbytes, "groups": gn_groups}
+    # ---- clip-parallel temporal convolution of the same level's tensor (Section 4.2), on its own:
+    # 3 taps, C -> C channels, bias; a dense contraction, priced against the bf16 matrix-core peak
+    conv_w, conv_b = synth.make_conv_weights(3, lvl.C, lvl.C, wl.seed + 50, "bf16", device=dev)
+    conv_info = B.dsattn_temporal_conv_info(wl.clip_len, wl.n_clips, lvl.P, lvl.C, lvl.C, 1)
+
+    def conv():
+        B.dsattn_temporal_conv(wl.clip_len, wl.n_clips, lvl.P, lvl.C, lvl.C, 1, L0["q"], conv_w,
+                               L0["o"], bias=conv_b, stream=stream)
+    conv()
+    g0.record(stream)
+    for _ in range(5):
+        conv()
+    g1.record(stream)
+    torch.cuda.synchronize()
+    conv_ms = g0.elapsed_time(g1) / 5
+    conv_tflops = conv_info["useful_flops"] / conv_ms / 1e9
+    temporal_conv = {"ms": round(conv_ms, 4), "TFLOPps": round(conv_tflops, 1),
+                     "useful_flops": conv_info["useful_flops"],
+                     "roofline": {"bound": "mfma", "achieved": round(conv_tflops, 1),
+                                  "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                  "frac": round(conv_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
+                     "launch": conv_info}
+    del conv_w, conv_b
     # restore O (the copy probe used it as scratch)
     step()
     torch.cuda.synchronize()
@@ -227,6 +251,7 @@ def main():
         "copy_probe_GBps": round(copy_gbps, 1),
         "gather_context": gather,
         "groupnorm": groupnorm,
+        "temporal_conv": temporal_conv,
         "device": torch.cuda.get_device_name(0),
         "roofline": roofline,
         "cpu_baseline": cpu,

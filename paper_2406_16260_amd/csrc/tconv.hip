@@ -11,13 +11,17 @@
 //
 // MFMA kernel.  A workgroup of 4 wavefronts (one per SIMD, 512 registers each) computes a
 // (64 MI) x (64 NJ) tile of Y; wavefront (wm, wn) owns a (32 MI) x (32 NJ) quarter as MI x NJ
-// accumulators of v_mfma_f32_32x32x16_bf16.  The contraction runs in steps of 64 channels of one
-// tap: the step's X rows and W rows go global -> registers -> LDS (double buffered, one barrier
-// per step) while the previous step is multiplied out of the other buffer.  LDS rows are 128 B
-// of data padded to 144 B, which makes both the 16-byte row writes and the 16-byte operand
-// reads (32 consecutive rows, same chunk) free of bank conflicts.  Workgroups are numbered so
-// that each XCD walks a contiguous run of tiles (all column tiles of a few neighbouring row
-// tiles): the W slabs and the rows shared between taps are then served by that XCD's L2.
+// accumulators of v_mfma_f32_32x32x16_bf16 (W rows as the A operand, X rows as the B operand).
+// The contraction runs in stages of 64 channels of one tap, taps innermost.  A stage's X rows
+// and W rows (one 128-byte cache line each) go from global memory straight into LDS with
+// buffer_load ... lds, into one of two slots, while the other slot is multiplied out; one
+// barrier per stage.  The LDS rows are unpadded (the load instruction fixes the layout) and
+// XOR-swizzled in 16-byte chunks, which keeps the operand reads free of bank conflicts.  The
+// matrix instructions, the LDS reads of the next fragments and the issue of the next stage's
+// loads are interleaved by hand.  Rows outside the video are zeroed by the buffer descriptor's
+// range check, not by code.  Workgroups are numbered so that each XCD walks a contiguous run of
+// tiles (all column tiles of a few neighbouring row tiles): the W slabs, and the X rows shared
+// between taps and column tiles, are then served by that XCD's L2.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -168,7 +172,13 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
     constexpr int NR = MI + NJ, NM = MI * NJ;
     constexpr int NKK = kBK / 16;
     static_assert(NKK % 2 == 0, "fragment slots alternate and must line up across stages");
-    constexpr int NLK = NL / 2;  // loads issued in each of the first two sub-steps
+    // The loads of the next stage may start as soon as the barrier has freed the other slot and
+    // must have landed by the next barrier; they are spread over the first kSpread multiplies
+    // after the barrier, one every few multiplies, so that the memory pipeline's queue never
+    // fills (a wavefront that cannot issue a load cannot issue multiplies either), and the last
+    // one still has the rest of the stage to land.
+    constexpr int TAIL = NM - NM / 2;   // multiplies of a stage's last sub-step after the barrier
+    constexpr int kSpread = TAIL + 2 * NM + NM / 2;
     auto read_frag = [&](const unsigned char *base, int kk, int slot, int r)
                          __attribute__((always_inline)) {
         if (r < MI)
@@ -178,16 +188,17 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
     };
     // multiplies [mlo, mhi) of the sub-step whose fragments are in `slot`; read r of the next
     // fragments (sub-step kk of `base`) goes before multiply mlo + floor(r (mhi - mlo) / NR)
-    // when do_reads; global load ld0 + q goes before multiply floor(q NM / NLK) when ld0 >= 0
+    // when do_reads; g0 is the number of multiplies since the barrier at multiply mlo: load q
+    // goes before the multiply that is number floor(q kSpread / NL) since the barrier
     auto mma_range = [&](int slot, int mlo, int mhi, bool do_reads, const unsigned char *base, int kk,
-                         int ld0) __attribute__((always_inline)) {
+                         int g0) __attribute__((always_inline)) {
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
             if (m < mlo || m >= mhi) continue;
 #pragma unroll
-            for (int q = 0; q < NLK; ++q)
-                if (ld0 >= 0 && (q * NM) / NLK == m) {
-                    issue_one(ld0 + q);
+            for (int q = 0; q < NL; ++q)
+                if ((q * kSpread) / NL == g0 + m - mlo) {
+                    issue_one(q);
                     __builtin_amdgcn_sched_barrier(0);
                 }
 #pragma unroll
@@ -203,36 +214,40 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
         }
     };
 
-    // prologue: stage 0 landed.  (Bare barriers: the wait before them is the only ordering
-    // needed, and a workgroup fence would add nothing.)
+    // prologue: stage 0 landed, the first loads of stage 1 issued as the loop's tail would have.
+    // (Bare barriers: the wait before them is the only ordering needed.)
     stage_setup(0);
 #pragma unroll
     for (int l = 0; l < NL; ++l) issue_one(l);
     __builtin_amdgcn_s_waitcnt(0);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
+    stage_setup(1);
+#pragma unroll
+    for (int q = 0; q < NL; ++q)
+        if ((q * kSpread) / NL < TAIL) issue_one(q);
 #pragma unroll
     for (int r = 0; r < NR; ++r) read_frag(smem, 0, 0, r);
 
     for (int ks = 0; ks < a.KS; ++ks) {
-        // the other slot was last read in stage ks - 1, which every wavefront has left
-        stage_setup(ks + 1);
-        __builtin_amdgcn_sched_barrier(0);
         const unsigned char *bufc = smem + (ks & 1) * BUF;
         const unsigned char *bufn = smem + ((ks + 1) & 1) * BUF;
 #pragma unroll
         for (int kk = 0; kk + 1 < NKK; ++kk)
-            mma_range(kk & 1, 0, NM, true, bufc, kk + 1, kk < 2 ? kk * NLK : -1);
+            mma_range(kk & 1, 0, NM, true, bufc, kk + 1, TAIL + kk * NM);
         // last sub-step: half of its multiplies, then the barrier (this wavefront's loads of
-        // stage ks + 1 have landed; after the barrier everybody's have), then the first
-        // fragments of the next stage interleaved with the other half.  After the last stage
+        // stage ks + 1 have landed; after the barrier everybody's have, and every wavefront
+        // has left slot ks % 2), then the first fragments of the next stage and the first
+        // loads of the stage after it interleaved with the other half.  After the last stage
         // those fragments are never used: the reads stay in bounds, and keeping them
         // unconditional keeps the multiplies out of divergent control flow.
-        mma_range((NKK - 1) & 1, 0, NM / 2, false, bufc, 0, -1);
+        mma_range((NKK - 1) & 1, 0, NM / 2, false, bufc, 0, TAIL + (NKK - 1) * NM);
         __builtin_amdgcn_s_waitcnt(0);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        mma_range((NKK - 1) & 1, NM / 2, NM, true, bufn, 0, -1);
+        stage_setup(ks + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_range((NKK - 1) & 1, NM / 2, NM, true, bufn, 0, 0);
     }
     // the loop's last barrier has retired every load (the last stage's were the out-of-range
     // ones of the stage past the end, which write zeros) and every operand read that matters
