@@ -239,6 +239,40 @@ int dsattn_temporal_conv_info(const dsattn_conv_desc *desc, dsattn_conv_info *in
 int dsattn_temporal_conv(const dsattn_conv_desc *desc, const void *X, const void *W,
                          const float *bias, void *Y, void *stream);
 
+/*
+ * The token-wise linear projections around the temporal attention (Section 4.2: queries, keys
+ * and values "are computed from tokens"; the paper gives no formula beyond that, these are the
+ * usual  Y_k = X W_k^T + b_k).  n_out weight sets are applied to the same X in one launch (3 for
+ * Q, K, V: X is read from HBM once for all of them; 1 for the output projection).  Because the
+ * projection is per token, projecting before or after a clip's context is gathered is the same.
+ * Runs the temporal convolution's matrix-core kernel as its one-tap case.
+ */
+typedef struct dsattn_linear_desc {
+    int64_t rows;      /* M >= 1 tokens (F * P), at most 2^31 - 1 */
+    int32_t c_in;      /* >= 1 */
+    int32_t c_out;     /* >= 1, the same for every weight set */
+    int32_t n_out;     /* 1 .. 4 weight sets */
+    int32_t io_dtype;  /* dsattn_dtype of X and W; products are accumulated in fp32 */
+    int32_t out_dtype; /* dsattn_dtype of every Y */
+    uint32_t flags;    /* DSATTN_FLAG_FORCE_GENERIC or 0 */
+} dsattn_linear_desc;
+
+/* The launch the library would make (host only); flops and bytes are those of all n_out sets. */
+int dsattn_linear_info(const dsattn_linear_desc *desc, dsattn_conv_info *info);
+
+/*
+ *   X    : device, [rows, c_in] of io_dtype, 16-byte aligned
+ *   W    : HOST array of n_out device pointers, each [c_out][c_in] of io_dtype, 16-byte aligned
+ *   bias : NULL, or HOST array of n_out device pointers, each [c_out] fp32 or NULL
+ *   Y    : HOST array of n_out device pointers, each [rows, c_out] of out_dtype, 16-byte aligned;
+ *          the outputs must not overlap X or each other
+ * The pointer arrays are read during the call only.  Runs on the current device; enqueues one
+ * kernel on `stream` (n_out kernels on the vector path); allocates nothing.
+ * Errors: EINVAL, EUNSUPPORTED (too large for the vector kernel), EHIP.
+ */
+int dsattn_linear(const dsattn_linear_desc *desc, const void *X, const void *const *W,
+                  const float *const *bias, void *const *Y, void *stream);
+
 /* Static description of a status code; never NULL. */
 const char *dsattn_strerror(int code);
 

@@ -8,7 +8,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRCS = [os.path.join(HERE, "dsattn_oracle.c"), os.path.join(HERE, "groupnorm_oracle.c"),
-        os.path.join(HERE, "tconv_oracle.c")]
+        os.path.join(HERE, "tconv_oracle.c"), os.path.join(HERE, "linear_oracle.c")]
 LIB = os.path.join(HERE, "liboracle_dsattn.so")
 
 

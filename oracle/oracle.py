@@ -37,6 +37,8 @@ def _load():
         lib.oracle_groupnorm.argtypes = [i64, i64, i64, i64, i64, ctypes.c_double, p, p, p, p, p, p]
         lib.oracle_temporal_conv.restype = ctypes.c_int
         lib.oracle_temporal_conv.argtypes = [i64, i64, i64, i64, i64, i64, p, p, p, p]
+        lib.oracle_linear.restype = ctypes.c_int
+        lib.oracle_linear.argtypes = [i64, i64, i64, p, p, p, p]
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_num_threads.argtypes = []
         _lib = lib
@@ -161,4 +163,25 @@ def temporal_conv(x, w, clip_len, n_clips, bias=None):
                                   y.ctypes.data)
     if rc != 0:
         raise ValueError(f"oracle_temporal_conv failed with {rc}")
+    return y
+
+
+def linear(x, w, bias=None):
+    """Token-wise projection (Section 4.2): x [..., C_in], w [C_out, C_in], bias [C_out] or None
+    -> y [..., C_out] float64."""
+    lib = _load()
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    c_out, c_in = w.shape
+    if x.shape[-1] != c_in:
+        raise ValueError("shape mismatch")
+    rows = x.size // c_in
+    b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float64)
+    if b is not None and b.shape != (c_out,):
+        raise ValueError("bias shape")
+    y = np.empty(x.shape[:-1] + (c_out,), dtype=np.float64)
+    rc = lib.oracle_linear(rows, c_in, c_out, x.ctypes.data, w.ctypes.data,
+                           None if b is None else b.ctypes.data, y.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"oracle_linear failed with {rc}")
     return y

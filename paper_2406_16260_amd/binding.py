@@ -29,7 +29,8 @@ EXPORTS = (
     "dsattn_plan", "dsattn_plan_destroy", "dsattn_plan_ctx_max", "dsattn_plan_ctx_indices",
     "dsattn_plan_launch_info", "dsattn_gather_context", "dsattn_forward", "dsattn_forward_ctx",
     "dsattn_copy_probe", "dsattn_strerror", "dsattn_last_error", "dsattn_groupnorm_workspace",
-    "dsattn_groupnorm", "dsattn_temporal_conv_info", "dsattn_temporal_conv",
+    "dsattn_groupnorm", "dsattn_temporal_conv_info", "dsattn_temporal_conv", "dsattn_linear_info",
+    "dsattn_linear",
 )
 
 
@@ -56,6 +57,14 @@ class DsattnConvDesc(ctypes.Structure):
         ("clip_len", ctypes.c_int32), ("n_clips", ctypes.c_int32), ("spatial", ctypes.c_int32),
         ("c_in", ctypes.c_int32), ("c_out", ctypes.c_int32), ("reach", ctypes.c_int32),
         ("io_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32), ("flags", ctypes.c_uint32),
+    ]
+
+
+class DsattnLinearDesc(ctypes.Structure):
+    _fields_ = [
+        ("rows", ctypes.c_int64), ("c_in", ctypes.c_int32), ("c_out", ctypes.c_int32),
+        ("n_out", ctypes.c_int32), ("io_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+        ("flags", ctypes.c_uint32),
     ]
 
 
@@ -134,6 +143,12 @@ def load():
                                               ctypes.POINTER(DsattnConvInfo)]
     lib.dsattn_temporal_conv.restype = ctypes.c_int
     lib.dsattn_temporal_conv.argtypes = [ctypes.POINTER(DsattnConvDesc), vp, vp, vp, vp, vp]
+    lib.dsattn_linear_info.restype = ctypes.c_int
+    lib.dsattn_linear_info.argtypes = [ctypes.POINTER(DsattnLinearDesc),
+                                       ctypes.POINTER(DsattnConvInfo)]
+    lib.dsattn_linear.restype = ctypes.c_int
+    lib.dsattn_linear.argtypes = [ctypes.POINTER(DsattnLinearDesc), vp, ctypes.POINTER(vp),
+                                  ctypes.POINTER(vp), ctypes.POINTER(vp), vp]
     lib.dsattn_groupnorm.restype = ctypes.c_int
     lib.dsattn_groupnorm.argtypes = [ctypes.POINTER(DsattnGnDesc), vp, vp, vp, vp, vp, vp,
                                      ctypes.c_size_t, vp]
@@ -310,3 +325,31 @@ def dsattn_temporal_conv(clip_len, n_clips, spatial, c_in, c_out, reach, X, W, Y
                           io_dtype if out_dtype is None else out_dtype, flags)
     _check(load().dsattn_temporal_conv(ctypes.byref(desc), _ptr(X), _ptr(W), _ptr(bias), _ptr(Y),
                                        _stream(stream)), "dsattn_temporal_conv")
+
+
+def dsattn_linear_info(rows, c_in, c_out, n_out, io_dtype=DSATTN_BF16, out_dtype=None, flags=0) -> dict:
+    desc = DsattnLinearDesc(rows, c_in, c_out, n_out, io_dtype,
+                            io_dtype if out_dtype is None else out_dtype, flags)
+    info = DsattnConvInfo()
+    _check(load().dsattn_linear_info(ctypes.byref(desc), ctypes.byref(info)), "dsattn_linear_info")
+    return info.as_dict()
+
+
+def _ptr_array(items, n):
+    arr = (ctypes.c_void_p * n)()
+    for i in range(n):
+        arr[i] = _ptr(items[i])
+    return arr
+
+
+def dsattn_linear(rows, c_in, c_out, X, Ws, Ys, biases=None, io_dtype=DSATTN_BF16, out_dtype=None,
+                  flags=0, stream=None):
+    """Ws, Ys (and biases, entries may be None): sequences of n_out tensors."""
+    n = len(Ws)
+    if len(Ys) != n or (biases is not None and len(biases) != n):
+        raise ValueError("Ws, Ys and biases must have the same length")
+    desc = DsattnLinearDesc(rows, c_in, c_out, n, io_dtype,
+                            io_dtype if out_dtype is None else out_dtype, flags)
+    _check(load().dsattn_linear(ctypes.byref(desc), _ptr(X), _ptr_array(Ws, n),
+                                None if biases is None else _ptr_array(biases, n),
+                                _ptr_array(Ys, n), _stream(stream)), "dsattn_linear")

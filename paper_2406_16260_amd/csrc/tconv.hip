@@ -45,15 +45,19 @@ constexpr int kRow = 128;     // bytes of one LDS row: the 64 channels of a stag
 constexpr int kSlots = 2;     // LDS ring: one stage in use, one on its way
 constexpr int kXcds = 8;
 
+constexpr int kMaxGroups = 4;  // weight sets applied to the same input in one launch
+
 struct ConvArgs {
-    const void *X, *W;
-    const float *bias;
-    void *Y;
+    const void *X;
+    const void *W[kMaxGroups];     // per group: [taps][c_out][c_in]
+    const float *bias[kMaxGroups]; // per group: [c_out] or null
+    void *Y[kMaxGroups];           // per group: [M][c_out]
+    int32_t groups;
     int64_t M;                 // rows = F * P
     int32_t P, Cin, Cout, n;
     int32_t KC;                // stages per tap = ceil(c_in / 64)
     int32_t KS;                // stages in all = taps * KC
-    int32_t tiles_n, tiles;    // column tiles, all tiles
+    int32_t tiles_n, tiles;    // column tiles per group, all tiles (row tiles x groups x column tiles)
     int32_t per_xcd;           // ceil(tiles / 8)
     int32_t w_bytes;           // taps * c_out * c_in * 2
 };
@@ -69,9 +73,14 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
     // workgroup -> tile: XCD x (= blockIdx % 8) walks tiles [x * per_xcd, (x + 1) * per_xcd)
     const int tile = (int)(blockIdx.x % kXcds) * a.per_xcd + (int)(blockIdx.x / kXcds);
     if (tile >= a.tiles) return;  // whole workgroup: no barrier has been reached yet
-    const int mt = tile / a.tiles_n, nt = tile - mt * a.tiles_n;
+    // all column tiles of all groups of one row tile are neighbours: they share the X rows
+    const int tiles_row = a.tiles_n * a.groups;
+    const int mt = tile / tiles_row, rem = tile - mt * tiles_row;
+    const int grp = rem / a.tiles_n, nt = rem - grp * a.tiles_n;
     const int64_t m0 = (int64_t)mt * BM;
     const int n0 = nt * BN;
+    const float *gbias = a.bias[grp];
+    void *gY = a.Y[grp];
 
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -96,7 +105,7 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
         (void *)((const __bf16 *)a.X + rb * a.Cin), 0,
         (int)min((a.M - rb) * a.Cin * 2, (int64_t)0x7fffffff), 0x00020000);
     const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)a.W, 0, (int)a.w_bytes, 0x00020000);
+        (void *)a.W[grp], 0, (int)a.w_bytes, 0x00020000);
     const int rowbytes = a.Cin * 2;
     constexpr uint32_t kOob = 0xfffffff0u;
     int xoff[GA], woff[GB];  // byte offset of this lane's row and chunk within the tile's rows
@@ -264,7 +273,7 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
     float *bl = (float *)(smem + BIAS_OFF) + wv * (32 * NJ);
 #pragma unroll
     for (int c = lane; c < 32 * NJ; c += 64)
-        bl[c] = (a.bias && cbase + c < a.Cout) ? a.bias[cbase + c] : 0.f;
+        bl[c] = (gbias && cbase + c < a.Cout) ? gbias[cbase + c] : 0.f;
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
 
@@ -300,7 +309,7 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
                 if (q < 32 * MI * CPR && mrow0 + row < a.M && cbase + pc * 8 < a.Cout) {
                     const uint2 lo = *(const uint2 *)(stg + row * SROW + pc * 16);
                     const uint2 hi = *(const uint2 *)(stg + row * SROW + pc * 16 + 8);
-                    *(uint4 *)((__bf16 *)a.Y + (mrow0 + row) * a.Cout + cbase + pc * 8) =
+                    *(uint4 *)((__bf16 *)gY + (mrow0 + row) * a.Cout + cbase + pc * 8) =
                         make_uint4(lo.x, lo.y, hi.x, hi.y);
                 }
             }
@@ -324,21 +333,21 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
                                  acc[i][j][4 * g + 2] + b[2], acc[i][j][4 * g + 3] + b[3]};
                 if (vec_ok) {  // c_out % 4 == 0 and co % 4 == 0: all four channels exist
                     if constexpr (OUT_F32) {
-                        *(f32x4 *)((float *)a.Y + m * a.Cout + co) = y;
+                        *(f32x4 *)((float *)gY + m * a.Cout + co) = y;
                     } else {
                         bf16x4 yb;
 #pragma unroll
                         for (int e = 0; e < 4; ++e) yb[e] = (__bf16)y[e];
-                        *(bf16x4 *)((__bf16 *)a.Y + m * a.Cout + co) = yb;
+                        *(bf16x4 *)((__bf16 *)gY + m * a.Cout + co) = yb;
                     }
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
                         if (co + e < a.Cout) {
                             if constexpr (OUT_F32)
-                                ((float *)a.Y)[m * a.Cout + co + e] = y[e];
+                                ((float *)gY)[m * a.Cout + co + e] = y[e];
                             else
-                                ((__bf16 *)a.Y)[m * a.Cout + co + e] = (__bf16)y[e];
+                                ((__bf16 *)gY)[m * a.Cout + co + e] = (__bf16)y[e];
                         }
                 }
             }
@@ -399,7 +408,7 @@ int conv_validate(const dsattn_conv_desc *d, const char *who)
 }
 
 // Tile shape: the variant that wastes the fewest output columns, then the fewest output rows.
-const ConvVariant *conv_pick(const dsattn_conv_desc &d, int64_t M)
+const ConvVariant *conv_pick(const dsattn_conv_desc &d, int64_t M, int groups = 1)
 {
     if (d.io_dtype != DSATTN_BF16 || d.c_in % 8 != 0 || (d.flags & DSATTN_FLAG_FORCE_GENERIC))
         return nullptr;
@@ -412,7 +421,7 @@ const ConvVariant *conv_pick(const dsattn_conv_desc &d, int64_t M)
     for (const ConvVariant &v : kConvVariants) {
         const int64_t bm = 64 * v.MI, bn = 64 * v.NJ;
         const int64_t tm = (M + bm - 1) / bm, tn = (d.c_out + bn - 1) / bn;
-        if (tm * tn > 0x7fffffffLL / 2) continue;
+        if (tm * tn * groups > 0x7fffffffLL / 2) continue;
         const double cost = (double)(tm * bm) * (double)(tn * bn);  // multiplied-out area
         if (!best || cost < best_cost) {
             best = &v;
@@ -428,6 +437,106 @@ int conv_lds_bytes(const ConvVariant &v)
 {
     return std::max(kSlots * (64 * v.MI + 64 * v.NJ) * kRow, 4 * 32 * v.MI * (64 * v.NJ + 8)) +
            4 * 32 * v.NJ * (int)sizeof(float);
+}
+
+// A linear layer over M rows is the one-tap case of the convolution (every row its own frame).
+int linear_as_conv(const dsattn_linear_desc *l, dsattn_conv_desc &d, int64_t &M, const char *who)
+{
+    if (!l) return fail(DSATTN_EINVAL, "%s: null descriptor", who);
+    if (l->rows < 1 || l->rows > 0x7fffffffLL || l->c_in < 1 || l->c_out < 1)
+        return fail(DSATTN_EINVAL, "%s: sizes must be positive (rows at most 2^31 - 1)", who);
+    if (l->n_out < 1 || l->n_out > kMaxGroups)
+        return fail(DSATTN_EINVAL, "%s: n_out %d outside [1, %d]", who, l->n_out, kMaxGroups);
+    d = dsattn_conv_desc{};
+    d.clip_len = 1;
+    d.n_clips = (int32_t)l->rows;
+    d.spatial = 1;
+    d.c_in = l->c_in;
+    d.c_out = l->c_out;
+    d.reach = 0;
+    d.io_dtype = l->io_dtype;
+    d.out_dtype = l->out_dtype;
+    d.flags = l->flags;
+    M = l->rows;
+    return conv_validate(&d, who);
+}
+
+// Launches the implicit-GEMM kernel (when `v`) or the vector kernel for `groups` weight sets
+// applied to the same X.  `d` describes one set; M = rows of X and of every Y.
+hipError_t conv_launch(const dsattn_conv_desc &d, int64_t M, const ConvVariant *v, int groups,
+                       const void *X, const void *const *W, const float *const *bias,
+                       void *const *Y, hipStream_t st)
+{
+    hipError_t e = hipSuccess;
+    if (v) {
+        const void *fn = v->fn[d.out_dtype == DSATTN_F32 ? 1 : 0];
+        const int lds = conv_lds_bytes(*v);
+        // the default cap on dynamic LDS is 64 KB: raised once per kernel and device
+        static std::mutex mu;
+        static uint64_t prepared[sizeof(kConvVariants) / sizeof(kConvVariants[0])][2] = {};
+        int dev = 0;
+        e = hipGetDevice(&dev);
+        if (e == hipSuccess && dev < 64) {
+            std::lock_guard<std::mutex> lock(mu);
+            uint64_t &mask = prepared[v - kConvVariants][d.out_dtype == DSATTN_F32 ? 1 : 0];
+            if (!(mask >> dev & 1)) {
+                e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+                if (e == hipSuccess) mask |= (uint64_t)1 << dev;
+            }
+        } else if (e == hipSuccess) {
+            e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        }
+        if (e != hipSuccess) return e;
+        ConvArgs a;
+        a.X = X;
+        for (int g = 0; g < kMaxGroups; ++g) {
+            a.W[g] = g < groups ? W[g] : nullptr;
+            a.bias[g] = g < groups && bias ? bias[g] : nullptr;
+            a.Y[g] = g < groups ? Y[g] : nullptr;
+        }
+        a.groups = groups;
+        a.M = M;
+        a.P = d.spatial;
+        a.Cin = d.c_in;
+        a.Cout = d.c_out;
+        a.n = d.reach;
+        a.KC = (d.c_in + kBK - 1) / kBK;
+        a.KS = (2 * d.reach + 1) * a.KC;
+        const int64_t bm = 64 * v->MI, bn = 64 * v->NJ;
+        a.tiles_n = (int32_t)((d.c_out + bn - 1) / bn);
+        a.tiles = (int32_t)(((M + bm - 1) / bm) * a.tiles_n * groups);
+        a.per_xcd = (a.tiles + kXcds - 1) / kXcds;
+        a.w_bytes = (int32_t)((2 * (int64_t)d.reach + 1) * d.c_out * d.c_in * 2);
+        void *params[] = {&a};
+        return hipLaunchKernel(fn, dim3((unsigned)(a.per_xcd * kXcds)), dim3(256), params,
+                               (size_t)lds, st);
+    }
+    const int64_t total = M * d.c_out;
+    const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    for (int g = 0; g < groups; ++g) {
+        const float *b = bias ? bias[g] : nullptr;
+        if (d.io_dtype == DSATTN_F32)
+            hipLaunchKernelGGL((tconv_generic_kernel<float, float>), grid, block, 0, st,
+                               (const float *)X, (const float *)W[g], b, (float *)Y[g], M, d.spatial,
+                               d.c_in, d.c_out, d.reach);
+        else if (d.out_dtype == DSATTN_F32)
+            hipLaunchKernelGGL((tconv_generic_kernel<__bf16, float>), grid, block, 0, st,
+                               (const __bf16 *)X, (const __bf16 *)W[g], b, (float *)Y[g], M,
+                               d.spatial, d.c_in, d.c_out, d.reach);
+        else
+            hipLaunchKernelGGL((tconv_generic_kernel<__bf16, __bf16>), grid, block, 0, st,
+                               (const __bf16 *)X, (const __bf16 *)W[g], b, (__bf16 *)Y[g], M,
+                               d.spatial, d.c_in, d.c_out, d.reach);
+    }
+    return hipGetLastError();
+}
+
+// Y must not overlap X: an output row is written while other workgroups still read X
+bool ranges_overlap(const void *a, int64_t abytes, const void *b, int64_t bbytes)
+{
+    const uintptr_t a0 = (uintptr_t)a, a1 = a0 + (uintptr_t)abytes;
+    const uintptr_t b0 = (uintptr_t)b, b1 = b0 + (uintptr_t)bbytes;
+    return a0 < b1 && b0 < a1;
 }
 
 }  // namespace
@@ -489,76 +598,74 @@ int dsattn_temporal_conv(const dsattn_conv_desc *desc, const void *X, const void
     const int64_t F = (int64_t)d.clip_len * d.n_clips;
     const int64_t M = F * d.spatial;
     const int64_t in_b = d.io_dtype == DSATTN_BF16 ? 2 : 4, out_b = d.out_dtype == DSATTN_BF16 ? 2 : 4;
-    {
-        // an output row is written while neighbouring input rows are still being read by others
-        const uintptr_t x0 = (uintptr_t)X, x1 = x0 + (uintptr_t)(M * d.c_in * in_b);
-        const uintptr_t y0 = (uintptr_t)Y, y1 = y0 + (uintptr_t)(M * d.c_out * out_b);
-        if (x0 < y1 && y0 < x1)
-            return fail(DSATTN_EINVAL, "dsattn_temporal_conv: Y overlaps X");
-    }
-    hipStream_t st = (hipStream_t)stream;
+    if (ranges_overlap(X, M * d.c_in * in_b, Y, M * d.c_out * out_b))
+        return fail(DSATTN_EINVAL, "dsattn_temporal_conv: Y overlaps X");
     const ConvVariant *v = conv_pick(d, M);
-    hipError_t e = hipSuccess;
-    if (v) {
-        const void *fn = v->fn[d.out_dtype == DSATTN_F32 ? 1 : 0];
-        const int lds = conv_lds_bytes(*v);
-        // the default cap on dynamic LDS is 64 KB: raised once per kernel and device
-        static std::mutex mu;
-        static uint64_t prepared[sizeof(kConvVariants) / sizeof(kConvVariants[0])][2] = {};
-        int dev = 0;
-        e = hipGetDevice(&dev);
-        if (e == hipSuccess && dev < 64) {
-            std::lock_guard<std::mutex> lock(mu);
-            uint64_t &mask = prepared[v - kConvVariants][d.out_dtype == DSATTN_F32 ? 1 : 0];
-            if (!(mask >> dev & 1)) {
-                e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-                if (e == hipSuccess) mask |= (uint64_t)1 << dev;
-            }
-        } else if (e == hipSuccess) {
-            e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        }
-        if (e == hipSuccess) {
-            ConvArgs a;
-            a.X = X;
-            a.W = W;
-            a.bias = bias;
-            a.Y = Y;
-            a.M = M;
-            a.P = d.spatial;
-            a.Cin = d.c_in;
-            a.Cout = d.c_out;
-            a.n = d.reach;
-            a.KC = (d.c_in + kBK - 1) / kBK;
-            a.KS = (2 * d.reach + 1) * a.KC;
-            const int64_t bm = 64 * v->MI, bn = 64 * v->NJ;
-            a.tiles_n = (int32_t)((d.c_out + bn - 1) / bn);
-            a.tiles = (int32_t)(((M + bm - 1) / bm) * a.tiles_n);
-            a.per_xcd = (a.tiles + kXcds - 1) / kXcds;
-            a.w_bytes = (int32_t)((2 * (int64_t)d.reach + 1) * d.c_out * d.c_in * 2);
-            void *params[] = {&a};
-            e = hipLaunchKernel(fn, dim3((unsigned)(a.per_xcd * kXcds)), dim3(256), params,
-                                (size_t)lds, st);
-        }
-    } else {
-        const int64_t total = M * d.c_out;
-        if ((total + 255) / 256 > 0x7fffffffLL)
-            return fail(DSATTN_EUNSUPPORTED, "dsattn_temporal_conv: too large for the generic kernel");
-        const dim3 grid((unsigned)((total + 255) / 256)), block(256);
-        if (d.io_dtype == DSATTN_F32)
-            hipLaunchKernelGGL((tconv_generic_kernel<float, float>), grid, block, 0, st,
-                               (const float *)X, (const float *)W, bias, (float *)Y, M, d.spatial,
-                               d.c_in, d.c_out, d.reach);
-        else if (d.out_dtype == DSATTN_F32)
-            hipLaunchKernelGGL((tconv_generic_kernel<__bf16, float>), grid, block, 0, st,
-                               (const __bf16 *)X, (const __bf16 *)W, bias, (float *)Y, M,
-                               d.spatial, d.c_in, d.c_out, d.reach);
-        else
-            hipLaunchKernelGGL((tconv_generic_kernel<__bf16, __bf16>), grid, block, 0, st,
-                               (const __bf16 *)X, (const __bf16 *)W, bias, (__bf16 *)Y, M,
-                               d.spatial, d.c_in, d.c_out, d.reach);
-        e = hipGetLastError();
-    }
+    if (!v && (M * d.c_out + 255) / 256 > 0x7fffffffLL)
+        return fail(DSATTN_EUNSUPPORTED, "dsattn_temporal_conv: too large for the generic kernel");
+    const hipError_t e = conv_launch(d, M, v, 1, X, &W, &bias, &Y, (hipStream_t)stream);
     if (e != hipSuccess) return fail(DSATTN_EHIP, "dsattn_temporal_conv: %s", hipGetErrorString(e));
+    return DSATTN_OK;
+}
+
+int dsattn_linear_info(const dsattn_linear_desc *desc, dsattn_conv_info *info)
+{
+    dsattn_conv_desc d;
+    int64_t M = 0;
+    const int rc = linear_as_conv(desc, d, M, "dsattn_linear_info");
+    if (rc != DSATTN_OK) return rc;
+    if (!info) return fail(DSATTN_EINVAL, "dsattn_linear_info: null output");
+    *info = dsattn_conv_info{};
+    const ConvVariant *v = conv_pick(d, M, desc->n_out);
+    info->block_threads = 256;
+    if (v) {
+        const int64_t bm = 64 * v->MI, bn = 64 * v->NJ;
+        const int64_t tiles = ((M + bm - 1) / bm) * ((d.c_out + bn - 1) / bn) * desc->n_out;
+        info->kernel = 1;
+        info->tile_m = (int32_t)bm;
+        info->tile_n = (int32_t)bn;
+        info->tile_k = kBK;
+        info->n_blocks = (int32_t)(((tiles + kXcds - 1) / kXcds) * kXcds);
+        info->lds_bytes = conv_lds_bytes(*v);
+    } else {
+        info->tile_n = 1;
+        info->tile_k = 1;
+        info->n_blocks = (int32_t)std::min<int64_t>((M * d.c_out + 255) / 256, 0x7fffffff);
+    }
+    const int64_t in_b = d.io_dtype == DSATTN_BF16 ? 2 : 4, out_b = d.out_dtype == DSATTN_BF16 ? 2 : 4;
+    info->useful_flops = 2 * M * d.c_in * d.c_out * desc->n_out;
+    info->algorithmic_bytes =
+        M * d.c_in * in_b + (int64_t)desc->n_out * (d.c_out * d.c_in * in_b + M * d.c_out * out_b);
+    return DSATTN_OK;
+}
+
+int dsattn_linear(const dsattn_linear_desc *desc, const void *X, const void *const *W,
+                  const float *const *bias, void *const *Y, void *stream)
+{
+    dsattn_conv_desc d;
+    int64_t M = 0;
+    const int rc = linear_as_conv(desc, d, M, "dsattn_linear");
+    if (rc != DSATTN_OK) return rc;
+    if (!X || !W || !Y) return fail(DSATTN_EINVAL, "dsattn_linear: null pointer");
+    const int64_t in_b = d.io_dtype == DSATTN_BF16 ? 2 : 4, out_b = d.out_dtype == DSATTN_BF16 ? 2 : 4;
+    if ((uintptr_t)X & 15u) return fail(DSATTN_EINVAL, "dsattn_linear: X must be 16-byte aligned");
+    for (int g = 0; g < desc->n_out; ++g) {
+        if (!W[g] || !Y[g]) return fail(DSATTN_EINVAL, "dsattn_linear: null pointer in set %d", g);
+        if (((uintptr_t)W[g] | (uintptr_t)Y[g]) & 15u)
+            return fail(DSATTN_EINVAL, "dsattn_linear: pointers must be 16-byte aligned");
+        if (bias && bias[g] && ((uintptr_t)bias[g] & 3u))
+            return fail(DSATTN_EINVAL, "dsattn_linear: bias must be 4-byte aligned");
+        if (ranges_overlap(X, M * d.c_in * in_b, Y[g], M * d.c_out * out_b))
+            return fail(DSATTN_EINVAL, "dsattn_linear: output %d overlaps X", g);
+        for (int h = 0; h < g; ++h)
+            if (ranges_overlap(Y[h], M * d.c_out * out_b, Y[g], M * d.c_out * out_b))
+                return fail(DSATTN_EINVAL, "dsattn_linear: outputs %d and %d overlap", h, g);
+    }
+    const ConvVariant *v = conv_pick(d, M, desc->n_out);
+    if (!v && (M * d.c_out + 255) / 256 > 0x7fffffffLL)
+        return fail(DSATTN_EUNSUPPORTED, "dsattn_linear: too large for the generic kernel");
+    const hipError_t e = conv_launch(d, M, v, desc->n_out, X, W, bias, Y, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(DSATTN_EHIP, "dsattn_linear: %s", hipGetErrorString(e));
     return DSATTN_OK;
 }
 

@@ -147,3 +147,46 @@ def test_pins_catch_planted_mistakes():
     xr = np.concatenate([x[:1], x, x[-1:]])
     rep = brute(xr, w, b, 1)[1:-1]
     assert np.abs(rep - ref).max() > 1e-3
+
+
+# ---------------------------------------------------------------- linear projections (Section 4.2)
+
+def test_linear_oracle_matches_library_matmul_and_closed_forms():
+    rng = np.random.default_rng(21)
+    x = rng.standard_normal((5, 3, 7))
+    w = rng.standard_normal((4, 7))
+    b = rng.standard_normal(4)
+    y = oracle.linear(x, w, bias=b)
+    np.testing.assert_allclose(y, x @ w.T + b, rtol=0, atol=1e-13)                 # numpy's matmul
+    ref = torch.nn.functional.linear(torch.from_numpy(x), torch.from_numpy(w), torch.from_numpy(b))
+    np.testing.assert_allclose(y, ref.numpy(), rtol=0, atol=1e-13)                 # the library layer
+    np.testing.assert_allclose(oracle.linear(x, w), x @ w.T, rtol=0, atol=1e-13)
+    # identity weights return the input; a single 1 at (co = 2, ci = 5) routes channel 5 to 2
+    np.testing.assert_array_equal(oracle.linear(x, np.eye(7)), x)
+    w1 = np.zeros((4, 7))
+    w1[2, 5] = 1.0
+    y1 = oracle.linear(x, w1)
+    np.testing.assert_array_equal(y1[..., 2], x[..., 5])
+    assert (np.delete(y1, 2, axis=-1) == 0).all()
+    # the one-tap temporal convolution is the same map
+    np.testing.assert_allclose(oracle.temporal_conv(x, w[None], 5, 1, bias=b), y, rtol=0, atol=1e-13)
+    # a transposed weight or a dropped bias is caught by the library pin
+    assert np.abs(oracle.linear(x, w) - ref.numpy()).max() > 1e-3
+    with pytest.raises(ValueError):
+        oracle.linear(x, w.T)
+
+
+def test_projection_commutes_with_gathering_context():
+    """Section 4.2 computes keys and values from the tokens of a clip's context; the projection is
+    per token, so gathering projected K equals projecting gathered tokens (why the attention's
+    inputs are projected tensors)."""
+    rng = np.random.default_rng(22)
+    F, P, C = 12, 2, 6
+    x = rng.standard_normal((F, P, C))
+    w = rng.standard_normal((C, C))
+    k = oracle.linear(x, w)
+    g = [0, 7, 11]
+    np.testing.assert_allclose(oracle.gather_context(k, 4, 3, 1, g),
+                               np.where(oracle.gather_context(np.ones((F, 1, 1)), 4, 3, 1, g) > 0,
+                                        oracle.linear(oracle.gather_context(x, 4, 3, 1, g), w), 0.0),
+                               rtol=0, atol=1e-13)

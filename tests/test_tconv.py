@@ -200,3 +200,133 @@ def test_conv_on_side_stream():
         B.dsattn_temporal_conv(16, 2, P, c, c, 1, x, w, y, bias=b, stream=s)
     s.synchronize()
     assert torch.equal(y, ref)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name,n_pos", [("C3", 2), ("C2", 3), ("C1", 4)])
+def test_conv_full_size_levels_sampled(name, n_pos):
+    """The level shapes bench.py times (C -> C channels, 3 taps, bias, bf16), inputs generated on
+    the device; the oracle runs on a sample of spatial positions over all frames (positions are
+    independent of each other, so every sampled output is exact)."""
+    wl = synth.WORKLOADS[name]
+    lv = wl.levels[0]
+    announce(f"conv full size {name} {lv.spatial} C={lv.C}")
+    x = synth.make_tensor(wl.F, lv.P, lv.C, wl.seed, wl.generator, "bf16", device=DEV)
+    w, b = synth.make_conv_weights(3, lv.C, lv.C, wl.seed + 50, "bf16", device=DEV)
+    info = B.dsattn_temporal_conv_info(wl.clip_len, wl.n_clips, lv.P, lv.C, lv.C, 1)
+    assert info["kernel"] == 1
+    y = run_conv(x, w, b, wl.clip_len, wl.n_clips, "bf16")
+    assert torch.isfinite(y.float()).all()
+    pos = sorted({0, lv.P - 1, *(((np.arange(n_pos) * lv.P) // n_pos).tolist())})
+    pidx = torch.as_tensor(pos, device=DEV)
+    ref = oracle.temporal_conv(x.index_select(1, pidx).to("cpu").to(torch.float64).numpy(),
+                               w.to("cpu").to(torch.float64).numpy(), wl.clip_len, wl.n_clips,
+                               bias=b.to("cpu").to(torch.float64).numpy())
+    check_conv(y.index_select(1, pidx), ref, "bf16", f"conv full size {name}")
+
+
+# ---------------------------------------------------------------- linear projections (dsattn_linear)
+
+def test_linear_rejects_bad_arguments():
+    lib = B.load()
+    info = B.DsattnConvInfo()
+
+    def desc(**kw):
+        d = dict(rows=100, c_in=64, c_out=64, n_out=3, io_dtype=B.DSATTN_BF16,
+                 out_dtype=B.DSATTN_BF16, flags=0)
+        d.update(kw)
+        return B.DsattnLinearDesc(**d)
+    for kw in (dict(rows=0), dict(rows=1 << 31), dict(c_in=0), dict(c_out=0), dict(n_out=0),
+               dict(n_out=5), dict(io_dtype=9), dict(flags=2),
+               dict(io_dtype=B.DSATTN_F32, out_dtype=B.DSATTN_BF16)):
+        d = desc(**kw)
+        assert lib.dsattn_linear_info(ctypes.byref(d), ctypes.byref(info)) == B.DSATTN_EINVAL, kw
+    d = desc()
+    vp3 = ctypes.c_void_p * 3
+    w, y = vp3(0x100000, 0x200000, 0x300000), vp3(0x400000, 0x500000, 0x600000)
+    assert lib.dsattn_linear(ctypes.byref(d), None, w, None, y, None) == B.DSATTN_EINVAL
+    assert lib.dsattn_linear(ctypes.byref(d), 0x1000, None, None, y, None) == B.DSATTN_EINVAL
+    assert lib.dsattn_linear(ctypes.byref(d), 0x1008, w, None, y, None) == B.DSATTN_EINVAL
+    assert lib.dsattn_linear(ctypes.byref(d), 0x1000, vp3(0x100000, None, 0x300000), None, y,
+                             None) == B.DSATTN_EINVAL
+    # two outputs overlapping (100 rows x 64 channels x 2 bytes = 12,800 bytes each)
+    assert lib.dsattn_linear(ctypes.byref(d), 0x1000, w, None, vp3(0x400000, 0x400000 + 12784, 0x600000),
+                             None) == B.DSATTN_EINVAL
+    assert "overlap" in B.dsattn_last_error()
+    # an output overlapping the input
+    assert lib.dsattn_linear(ctypes.byref(d), 0x400000, w, None, y, None) == B.DSATTN_EINVAL
+
+
+def test_linear_info_counts():
+    # Q, K, V of the headline level in one launch: 15 column tiles per row tile
+    i = B.dsattn_linear_info(2304 * 160, 1280, 1280, 3)
+    assert i["kernel"] == 1 and i["tile_n"] in (256, 320)
+    tiles = (2304 * 160 // i["tile_m"]) * (1280 // i["tile_n"]) * 3
+    assert tiles <= i["n_blocks"] < tiles + 8
+    assert i["useful_flops"] == 2 * 2304 * 160 * 1280 * 1280 * 3
+    assert i["algorithmic_bytes"] == 2304 * 160 * 1280 * 2 * 4 + 3 * 1280 * 1280 * 2
+    assert B.dsattn_linear_info(100, 64, 64, 1, io_dtype=B.DSATTN_F32)["kernel"] == 0
+
+
+def linear_case(rows, c_in, c_out, n_out, dtype="bf16", out_dtype="bf16", flags=0, bias=True, seed=90):
+    x = synth.make_tensor(rows, 1, c_in, seed, "iid", dtype).to(DEV).reshape(rows, c_in)
+    ws, bs = [], []
+    for k in range(n_out):
+        w, b = synth.make_conv_weights(1, c_out, c_in, seed + 1 + k, dtype)
+        ws.append(w.reshape(c_out, c_in).to(DEV))
+        bs.append(b.to(DEV) if bias and k != 1 else None)   # the second set goes without a bias
+    ys = [torch.full((rows, c_out), float("nan"), dtype=synth.torch_dtype(out_dtype), device=DEV)
+          for _ in range(n_out)]
+    info = B.dsattn_linear_info(rows, c_in, c_out, n_out, io_dtype=U.dt_code(dtype),
+                                out_dtype=U.dt_code(out_dtype), flags=flags)
+    announce(f"linear rows={rows} {c_in}->{c_out} x{n_out} {dtype}->{out_dtype} kernel={info['kernel']} "
+             f"tile={info['tile_m']}x{info['tile_n']}")
+    B.dsattn_linear(rows, c_in, c_out, x, ws, ys, biases=bs if bias else None,
+                    io_dtype=U.dt_code(dtype), out_dtype=U.dt_code(out_dtype), flags=flags)
+    torch.cuda.synchronize()
+    xn = x.to("cpu").to(torch.float64).numpy()
+    for k in range(n_out):
+        ref = oracle.linear(xn, ws[k].to("cpu").to(torch.float64).numpy(),
+                            bias=None if bs[k] is None else bs[k].to("cpu").to(torch.float64).numpy())
+        check_conv(ys[k], ref, out_dtype, f"linear set {k}")
+    return info
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("rows,c_in,c_out,n_out", [
+    (700, 128, 256, 3),      # Q, K, V: a row tail, one column tile per set
+    (513, 320, 320, 3),      # the 320-wide tile
+    (300, 72, 200, 2),       # channel and column tails
+    (1000, 1280, 1280, 1),   # the output projection of the headline level
+    (64, 64, 40, 4),
+])
+def test_linear_mfma_matches_oracle(rows, c_in, c_out, n_out):
+    info = linear_case(rows, c_in, c_out, n_out)
+    assert info["kernel"] == 1
+
+
+@pytest.mark.gpu
+def test_linear_other_paths_match_oracle():
+    assert linear_case(50, 12, 9, 3, dtype="f32", out_dtype="f32")["kernel"] == 0
+    assert linear_case(90, 64, 64, 2, flags=B.DSATTN_FLAG_FORCE_GENERIC)["kernel"] == 0
+    assert linear_case(300, 128, 128, 3, out_dtype="f32", bias=False)["kernel"] == 1
+
+
+@pytest.mark.gpu
+def test_projected_qkv_feed_the_attention():
+    """X -> (Q, K, V) in one launch -> Dual-scope attention, each stage against the oracle on the
+    values the previous stage actually produced (bf16 tensors between the stages)."""
+    clip_len, n_clips, w, P, h, D = 16, 3, 2, 3, 2, 160
+    F, C = clip_len * n_clips, h * D
+    x = synth.make_tensor(F, P, C, 31, "correlated", "bf16").to(DEV)
+    ws = [synth.make_conv_weights(1, C, C, 32 + k, "bf16")[0].reshape(C, C).to(DEV) for k in range(3)]
+    q, k, v = (torch.empty_like(x) for _ in range(3))
+    B.dsattn_linear(F * P, C, C, x, ws, [q, k, v])
+    torch.cuda.synchronize()
+    xn = x.to("cpu").to(torch.float64).numpy()
+    for t, wt in zip((q, k, v), ws):
+        check_conv(t, oracle.linear(xn, wt.to("cpu").to(torch.float64).numpy()), "bf16", "projection")
+    g = [0, 20, 47]
+    o, info = U.library_forward(q, k, v, clip_len, n_clips, w, h, g)
+    assert info["kernel"] == 1
+    U.assert_parity(o, U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g), "bf16", what="attention")
