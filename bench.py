@@ -204,6 +204,31 @@ def main():
                                   "frac": round(conv_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
                      "launch": conv_info}
     del conv_w, conv_b
+    # ---- Q, K, V projections of the same level's tokens in one launch (Section 4.2: keys and values
+    # are computed from the tokens), C -> C each, no bias: the convolution kernel's one-tap case
+    proj_w = [synth.make_conv_weights(1, lvl.C, lvl.C, wl.seed + 60 + t, "bf16", device=dev)[0]
+              .reshape(lvl.C, lvl.C) for t in range(3)]
+    proj_y = [torch.empty_like(L0["q"]) for _ in range(3)]
+    rows = wl.F * lvl.P
+    proj_info = B.dsattn_linear_info(rows, lvl.C, lvl.C, 3)
+
+    def proj():
+        B.dsattn_linear(rows, lvl.C, lvl.C, L0["q"], proj_w, proj_y, stream=stream)
+    proj()
+    g0.record(stream)
+    for _ in range(5):
+        proj()
+    g1.record(stream)
+    torch.cuda.synchronize()
+    proj_ms = g0.elapsed_time(g1) / 5
+    proj_tflops = proj_info["useful_flops"] / proj_ms / 1e9
+    qkv_projection = {"ms": round(proj_ms, 4), "TFLOPps": round(proj_tflops, 1),
+                      "useful_flops": proj_info["useful_flops"],
+                      "roofline": {"bound": "mfma", "achieved": round(proj_tflops, 1),
+                                   "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                   "frac": round(proj_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
+                      "launch": proj_info}
+    del proj_w, proj_y
     # restore O (the copy probe used it as scratch)
     step()
     torch.cuda.synchronize()
@@ -252,6 +277,7 @@ def main():
         "gather_context": gather,
         "groupnorm": groupnorm,
         "temporal_conv": temporal_conv,
+        "qkv_projection": qkv_projection,
         "device": torch.cuda.get_device_name(0),
         "roofline": roofline,
         "cpu_baseline": cpu,

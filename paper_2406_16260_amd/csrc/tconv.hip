@@ -228,6 +228,18 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
     stage_setup(0);
 #pragma unroll
     for (int l = 0; l < NL; ++l) issue_one(l);
+    {
+        // the bias of this wavefront's 32 NJ channels goes into LDS now (zeros where there is
+        // no bias or no channel), behind everything the loop touches: the stores of the
+        // epilogue then depend on no global load
+        constexpr int kStageBytes = 4 * 32 * MI * (64 * NJ + 8);
+        constexpr int kBiasOff = (kSlots * BUF > kStageBytes) ? kSlots * BUF : kStageBytes;
+        float *bw = (float *)(smem + kBiasOff) + wv * (32 * NJ);
+        const int cb = n0 + wn * 32 * NJ;
+#pragma unroll
+        for (int c = lane; c < 32 * NJ; c += 64)
+            bw[c] = (gbias && cb + c < a.Cout) ? gbias[cb + c] : 0.f;
+    }
     __builtin_amdgcn_s_waitcnt(0);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
@@ -263,19 +275,12 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
 
     // epilogue: accumulator element e of lane l is output channel 8 (e / 4) + 4 (l / 32) + e % 4
     // and row l % 32 of its block: four consecutive channels per lane and e / 4.
-    // The bias of the wavefront's 32 NJ channels goes through LDS once (zeros where there is no
-    // bias or no channel), so that the stores below depend on no global load.
     constexpr int SROW = 64 * NJ + 8;
     constexpr int STAGE = 32 * MI * SROW;
     constexpr int BIAS_OFF = (kSlots * BUF > 4 * STAGE) ? kSlots * BUF : 4 * STAGE;
     const int cbase = n0 + wn * 32 * NJ;     // first channel of this wavefront's part
     const int64_t mrow0 = m0 + wm * 32 * MI;  // first row of this wavefront's part
-    float *bl = (float *)(smem + BIAS_OFF) + wv * (32 * NJ);
-#pragma unroll
-    for (int c = lane; c < 32 * NJ; c += 64)
-        bl[c] = (gbias && cbase + c < a.Cout) ? gbias[cbase + c] : 0.f;
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+    const float *bl = (const float *)(smem + BIAS_OFF) + wv * (32 * NJ);  // written in the prologue
 
     if constexpr (!OUT_F32) {
         if ((a.Cout & 7) == 0) {
