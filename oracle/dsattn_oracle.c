@@ -41,6 +41,11 @@
  *   query of frame a only if |f - a| <= r; hidden keys get weight exactly 0.
  *   Global keys are always visible.  window < 0 switches this off (every query
  *   of the clip sees the clip's whole local list).
+ *   Optional set union (Section 4.2 first writes the key set of a query as the
+ *   union of its local neighbours and the global frames, before turning to the
+ *   concatenation used in practice): with dedup a global entry whose frame the
+ *   query already sees (as a visible local key, or as an earlier global entry)
+ *   is dropped, so that no frame counts twice.
  *   No other mask, no positional term.  Outputs of the clips are concatenated along
  *   frames (Section 4.1, v_out = Concat), i.e. O has the layout of Q.
  *
@@ -127,7 +132,7 @@ int oracle_ctx_indices(int64_t clip_len, int64_t n_clips, int64_t w,
 int oracle_forward(int64_t clip_len, int64_t n_clips, int64_t w,
                    int64_t P, int64_t h, int64_t D,
                    const int32_t *global_idx, int64_t n_global, double scale,
-                   double bias_local, double bias_global, int64_t window,
+                   double bias_local, double bias_global, int64_t window, int dedup,
                    const double *Q, const double *K, const double *V,
                    double *O, double *weights)
 {
@@ -175,6 +180,15 @@ int oracle_forward(int64_t clip_len, int64_t n_clips, int64_t w,
                                 int64_t dist = (int64_t)ctx[j] - a;
                                 if (dist < 0) dist = -dist;
                                 if (dist > window) s[j] = -INFINITY; /* hidden: exp gives 0 */
+                            }
+                            if (dedup && j >= L - n_global) {
+                                /* set union: a global entry is dropped if its frame is already
+                                   among the keys this query sees, i.e. among the visible local
+                                   keys or among the global entries before it */
+                                int seen = 0;
+                                for (int64_t jj = 0; jj < j && !seen; ++jj)
+                                    if (ctx[jj] == ctx[j] && s[jj] != -INFINITY) seen = 1;
+                                if (seen) s[j] = -INFINITY;
                             }
                             if (s[j] > m) m = s[j];
                         }

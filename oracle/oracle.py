@@ -30,7 +30,7 @@ def _load():
         lib.oracle_ctx_indices.argtypes = [i64, i64, i64, p, i64, i64, p, p]
         lib.oracle_forward.restype = ctypes.c_int
         lib.oracle_forward.argtypes = [i64, i64, i64, i64, i64, i64, p, i64, ctypes.c_double,
-                                       ctypes.c_double, ctypes.c_double, i64, p, p, p, p, p]
+                                       ctypes.c_double, ctypes.c_double, i64, ctypes.c_int, p, p, p, p, p]
         lib.oracle_gather_context.restype = ctypes.c_int
         lib.oracle_gather_context.argtypes = [i64, i64, i64, p, i64, i64, p, p]
         lib.oracle_groupnorm.restype = ctypes.c_int
@@ -73,11 +73,12 @@ def ctx_indices(clip_len, n_clips, w, global_idx):
 
 
 def forward(q, k, v, clip_len, n_clips, w, global_idx, scale=0.0, return_weights=False,
-            bias_local=0.0, bias_global=0.0, window=-1):
+            bias_local=0.0, bias_global=0.0, window=-1, dedup=False):
     """q, k, v: arrays [F, P, h, D] (any float dtype; converted exactly to float64).
 
     bias_local / bias_global: scope weights of Section 5.1 as additive logit biases.
     window: sliding-window radius for local keys (Section 4.2), < 0 for none.
+    dedup: set union instead of concatenation (Section 4.2): no frame counts twice.
     Returns O [F, P, h, D] float64, and the weights [F, P, h, lk_max] if asked.
     """
     lib = _load()
@@ -96,7 +97,8 @@ def forward(q, k, v, clip_len, n_clips, w, global_idx, scale=0.0, return_weights
         wts = np.empty((F, P, h, lk), dtype=np.float64)
         wp = wts.ctypes.data
     rc = lib.oracle_forward(clip_len, n_clips, w, P, h, D, gp, g.size, float(scale),
-                            float(bias_local), float(bias_global), int(window), q.ctypes.data,
+                            float(bias_local), float(bias_global), int(window), int(bool(dedup)),
+                            q.ctypes.data,
                             k.ctypes.data, v.ctypes.data, o.ctypes.data, wp)
     if rc != 0:
         raise ValueError(f"oracle_forward failed with {rc}")

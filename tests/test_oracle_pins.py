@@ -52,7 +52,7 @@ def test_ctx_lists_match_hand_derived(case):
     assert (idx[clip, ln[clip]:] == -1).all()
     # the brute force builds its list per query frame: every frame of the clip agrees
     for a in range(clip * clip_len, (clip + 1) * clip_len):
-        assert brute.key_frames(a, clip_len, n_clips, w, g) == expected
+        assert brute.key_frames(a, clip_len, n_clips, w, g)[0] == expected
 
 
 def test_ctx_rejects_bad_arguments():
@@ -121,7 +121,7 @@ def test_per_clip_library_attention(shape):
         # the list comes from the hand-derived fixture where there is one, else from the
         # brute force's own list builder (never from the C oracle under test)
         lst = golden.get((clip_len, n_clips, w, tuple(g), i),
-                         brute.key_frames(i * clip_len, clip_len, n_clips, w, g))
+                         brute.key_frames(i * clip_len, clip_len, n_clips, w, g)[0])
         rows = slice(i * clip_len, (i + 1) * clip_len)
         for p in range(P):
             for hd in range(h):
@@ -380,3 +380,77 @@ def test_gather_context_is_index_select():
     assert np.array_equal(out[0, :8], x[golden_clip0])
     assert (out[0, 8:] == 0).all()
     assert np.array_equal(out[1], x[golden_clip1])
+
+
+# ---------------------------------------------------------------- set union instead of Concat (Section 4.2)
+
+def test_dedup_global_pins():
+    """With dedup the key set of a query is the union of Section 4.2's formula: no frame twice."""
+    rng = np.random.default_rng(77)
+    clip_len, n_clips, w, P, h, D = 4, 5, 1, 2, 2, 3
+    F = clip_len * n_clips
+    q, k, v = (rng.standard_normal((F, P, h, D)) for _ in range(3))
+    scale = 0.9
+    g = [0, 4, 4, 17, 9, 0]          # repeats inside G, and frames inside some clips' local range
+    got = oracle.forward(q, k, v, clip_len, n_clips, w, g, scale=scale, dedup=True)
+    # (1) the separately written brute force over explicit union lists
+    np.testing.assert_allclose(got, np.array(brute.forward(q, k, v, clip_len, n_clips, w, g, scale=scale,
+                                                           dedup=True)), rtol=0, atol=1e-12)
+    # (2) per clip it is plain attention over the deduplicated list: library routine
+    for i in range(n_clips):
+        lo, hi = max(0, i * clip_len - w), min(F, (i + 1) * clip_len + w)
+        frames = list(range(lo, hi))
+        for f in g:
+            if f not in frames:
+                frames.append(f)
+        idx = torch.as_tensor(frames)
+        qt = torch.from_numpy(q[i * clip_len:(i + 1) * clip_len]).permute(1, 2, 0, 3)   # [P, h, Fc, D]
+        kt = torch.from_numpy(k).index_select(0, idx).permute(1, 2, 0, 3)
+        vt = torch.from_numpy(v).index_select(0, idx).permute(1, 2, 0, 3)
+        ref = torch.nn.functional.scaled_dot_product_attention(qt, kt, vt, scale=scale)
+        np.testing.assert_allclose(got[i * clip_len:(i + 1) * clip_len], ref.permute(2, 0, 1, 3).numpy(),
+                                   rtol=0, atol=1e-12)
+    # (3) it differs from the concatenation exactly where a frame is listed twice
+    cat = oracle.forward(q, k, v, clip_len, n_clips, w, g, scale=scale)
+    assert np.abs(cat - got).max() > 1e-3
+    # (4) a global set that repeats nothing and overlaps no clip's range: the flag changes nothing
+    wide = oracle.forward(q, k, v, 4, 5, 0, [], scale=scale, dedup=True)
+    np.testing.assert_array_equal(wide, oracle.forward(q, k, v, 4, 5, 0, [], scale=scale))
+    g1 = [19]
+    a_ = oracle.forward(q, k, v, clip_len, n_clips, w, g1, scale=scale, dedup=True)
+    b_ = oracle.forward(q, k, v, clip_len, n_clips, w, g1, scale=scale)
+    np.testing.assert_array_equal(a_[:14], b_[:14])          # clips 0..2 and frames 12, 13 of clip 3 ...
+    assert np.abs(a_[16:] - b_[16:]).max() > 1e-6            # ... but clip 4 holds frame 19 itself
+    # (5) a global set inside clip 0's range: clip 0 attends as if there were no global set
+    g0 = [0, 2, 4]
+    d0 = oracle.forward(q, k, v, clip_len, n_clips, w, g0, scale=scale, dedup=True)
+    none = oracle.forward(q, k, v, clip_len, n_clips, w, [], scale=scale)
+    np.testing.assert_allclose(d0[:clip_len], none[:clip_len], rtol=0, atol=1e-14)
+    # (6) weights: the dropped entries get exactly 0, the rest still sum to 1
+    _, wts = oracle.forward(q, k, v, clip_len, n_clips, w, g, scale=scale, dedup=True, return_weights=True)
+    np.testing.assert_allclose(wts.sum(axis=-1), 1.0, rtol=0, atol=1e-12)
+    idx, ln = oracle.ctx_indices(clip_len, n_clips, w, g)
+    for i in range(n_clips):
+        row = idx[i, :ln[i]].tolist()
+        for j, f in enumerate(row):
+            dropped = j >= ln[i] - len(g) and f in row[:j]
+            zero = (wts[i * clip_len:(i + 1) * clip_len, :, :, j] == 0).all()
+            assert zero == dropped, (i, j, f)
+
+
+def test_dedup_with_sliding_window_is_per_query():
+    """Under the window a local copy the query cannot see does not shadow the global copy."""
+    rng = np.random.default_rng(78)
+    clip_len, n_clips, w, P, h, D = 4, 3, 2, 1, 1, 2
+    q, k, v = (rng.standard_normal((12, P, h, D)) for _ in range(3))
+    g = [5, 1]
+    got = oracle.forward(q, k, v, clip_len, n_clips, w, g, scale=1.0, window=1, dedup=True)
+    np.testing.assert_allclose(got, np.array(brute.forward(q, k, v, clip_len, n_clips, w, g, scale=1.0,
+                                                           window=1, dedup=True)), rtol=0, atol=1e-12)
+    _, wts = oracle.forward(q, k, v, clip_len, n_clips, w, g, scale=1.0, window=1, dedup=True,
+                            return_weights=True)
+    idx, ln = oracle.ctx_indices(clip_len, n_clips, w, g)
+    jg5 = ln[1] - 2   # position of global frame 5 in clip 1's list (frames 2..9, then 5, 1)
+    # query frame 4 sees local 3..5: global 5 is dropped; query frame 7 sees 6..8: global 5 stays
+    assert wts[4, 0, 0, jg5] == 0 and wts[5, 0, 0, jg5] == 0 and wts[6, 0, 0, jg5] == 0
+    assert wts[7, 0, 0, jg5] > 0

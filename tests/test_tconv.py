@@ -330,3 +330,40 @@ def test_projected_qkv_feed_the_attention():
     o, info = U.library_forward(q, k, v, clip_len, n_clips, w, h, g)
     assert info["kernel"] == 1
     U.assert_parity(o, U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g), "bf16", what="attention")
+
+
+def test_conv_falls_back_when_offsets_would_not_fit_32_bits():
+    # the matrix-core kernel addresses a tile's X rows and all of W with 32-bit byte offsets
+    assert B.dsattn_temporal_conv_info(16, 4, 40000, 1280, 64, 16)["kernel"] == 0   # reach x P rows x c_in
+    assert B.dsattn_temporal_conv_info(16, 4, 4, 16384, 16384, 3)["kernel"] == 0    # W of 3.75 GB
+    assert B.dsattn_temporal_conv_info(16, 4, 40000, 1280, 64, 1)["kernel"] == 1
+
+
+@pytest.mark.gpu
+def test_conv_and_linear_in_hip_graph_replays():
+    """After one eager call on the device (which raises the kernel's LDS limit once), both entry
+    points are a single kernel launch and can be captured and replayed."""
+    F, P, c = 32, 6, 128
+    x = synth.make_tensor(F, P, c, 15, "iid", "bf16").to(DEV)
+    w, b = (t.to(DEV) for t in synth.make_conv_weights(3, c, c, 16, "bf16"))
+    ws = [synth.make_conv_weights(1, c, c, 17 + k, "bf16")[0].reshape(c, c).to(DEV) for k in range(3)]
+    y_eager = run_conv(x, w, b, 16, 2, "bf16")
+    p_eager = [torch.empty_like(x) for _ in range(3)]
+    B.dsattn_linear(F * P, c, c, x, ws, p_eager)
+    torch.cuda.synchronize()
+    y = torch.zeros_like(y_eager)
+    ps = [torch.zeros_like(x) for _ in range(3)]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.dsattn_temporal_conv(16, 2, P, c, c, 1, x, w, y, bias=b)
+        B.dsattn_linear(F * P, c, c, x, ws, ps)
+    for rep in range(3):
+        y.fill_(0)                             # eager work between replays
+        for t in ps:
+            t.fill_(0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_eager), f"replay {rep}: convolution differs from the eager result"
+        for t, e in zip(ps, p_eager):
+            assert torch.equal(t, e), f"replay {rep}: projection differs from the eager result"
