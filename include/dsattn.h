@@ -55,6 +55,12 @@ typedef enum dsattn_dtype { DSATTN_F32 = 0, DSATTN_BF16 = 1 } dsattn_dtype;
                                          dsattn_desc.window (Section 4.2: the local context as the
                                          neighbouring frames of the query frame) */
 
+#define DSATTN_FLAG_DEDUP_GLOBAL 4u   /* set union instead of concatenation (Section 4.2 writes the
+                                         key set of a query as the union of its local neighbours and
+                                         the global frames): a global entry whose frame the query
+                                         already sees, as a visible local key or as an earlier
+                                         global entry, is dropped, so that no frame counts twice */
+
 /* Problem statement, in the paper's terms. */
 typedef struct dsattn_desc {
     int32_t clip_len;   /* F_clip >= 1                              (Section 4) */

@@ -24,6 +24,7 @@ DSATTN_F32 = 0
 DSATTN_BF16 = 1
 DSATTN_FLAG_FORCE_GENERIC = 1
 DSATTN_FLAG_SLIDING_WINDOW = 2
+DSATTN_FLAG_DEDUP_GLOBAL = 4
 
 EXPORTS = (
     "dsattn_plan", "dsattn_plan_destroy", "dsattn_plan_ctx_max", "dsattn_plan_ctx_indices",

@@ -104,6 +104,8 @@ int dsattn_plan(const dsattn_desc *desc, const int32_t *global_idx, int32_t n_gl
         return fail(DSATTN_EINVAL, "dsattn_plan: scale is not finite");
     if (!std::isfinite(d.bias_local) || !std::isfinite(d.bias_global))
         return fail(DSATTN_EINVAL, "dsattn_plan: scope biases must be finite");
+    if (d.flags & ~(DSATTN_FLAG_FORCE_GENERIC | DSATTN_FLAG_SLIDING_WINDOW | DSATTN_FLAG_DEDUP_GLOBAL))
+        return fail(DSATTN_EINVAL, "dsattn_plan: unknown flag bits 0x%x", d.flags);
     if ((d.flags & DSATTN_FLAG_SLIDING_WINDOW) && d.window < 0)
         return fail(DSATTN_EINVAL, "dsattn_plan: sliding window radius must be >= 0");
     const int64_t F = (int64_t)d.clip_len * d.n_clips;

@@ -51,6 +51,8 @@ bool mfma_plan(dsattn_plan_t &pl)
     // global key tiles: variants exist for 0, 1 and 4 tiles; a partly used tile is masked
     if (G > 64) return false;
     const int NGT = G == 0 ? 0 : (G <= 16 ? 1 : 4);
+    // the set-union option is built into the variants with one global key tile only
+    if ((d.flags & DSATTN_FLAG_DEDUP_GLOBAL) && NGT == 4) return false;
     const int R = 16 + 2 * d.local_ctx;
     const int NLT = (R + 15) / 16;
     const bool out_f32 = d.out_dtype == DSATTN_F32;
@@ -187,6 +189,14 @@ hipError_t launch_mfma(const dsattn_plan_t &pl, const void *Q, const void *K, co
     a.FS = (int64_t)d.spatial * pl.C;
     a.sc = pl.scale * 1.4426950408889634f;
     a.gshift = (d.bias_global - d.bias_local) / pl.scale;
+    a.dedup = (d.flags & DSATTN_FLAG_DEDUP_GLOBAL) ? 1 : 0;
+    a.gdup = 0;  // entries that repeat an earlier one (the kernel is used for at most 64 entries)
+    for (size_t j = 0; j < pl.global_idx.size() && j < 64; ++j)
+        for (size_t jj = 0; jj < j; ++jj)
+            if (pl.global_idx[jj] == pl.global_idx[j]) {
+                a.gdup |= (uint64_t)1 << j;
+                break;
+            }
 
     // the grid must be exactly chunks x workgroups-per-chunk, each workgroup wpb whole row groups
     const int NC = (d.n_clips + a.M - 1) / a.M;

@@ -126,7 +126,7 @@ __global__ __launch_bounds__(64) void generic_attn_kernel(
     const Tin *__restrict__ Q, const Tin *__restrict__ K, const Tin *__restrict__ V,
     Tout *__restrict__ O, const int32_t *__restrict__ ctx_idx, const int32_t *__restrict__ ctx_len,
     int clip_len, int P, int h, int D, int lk_max, float scale, int ctx_mode, int n_global,
-    float bias_local, float bias_global, int window)
+    float bias_local, float bias_global, int window, int dedup)
 {
     extern __shared__ float smem[];
     float *sp = smem;
@@ -160,6 +160,16 @@ __global__ __launch_bounds__(64) void generic_attn_kernel(
             float s = dot * scale + (j < L - n_global ? bias_local : bias_global);
             // sliding window: a local key further than `window` frames from the query is hidden
             if (window >= 0 && j < L - n_global && abs(ctx[j] - a) > window) s = -INFINITY;
+            // set union: a global entry is dropped if the query already sees its frame, as a
+            // visible local key (the local part is the frame range ctx[0] .. ctx[nl - 1]) or as an
+            // earlier global entry
+            if (dedup && j >= L - n_global) {
+                const int nl = L - n_global, f = ctx[j];
+                bool seen = nl > 0 && f >= ctx[0] && f <= ctx[nl - 1] &&
+                            (window < 0 || abs(f - a) <= window);
+                for (int jj = nl; jj < j && !seen; ++jj) seen = ctx[jj] == f;
+                if (seen) s = -INFINITY;
+            }
             sp[j] = s;
             m = fmaxf(m, s);
         }
@@ -211,7 +221,7 @@ hipError_t launch_generic(const dsattn_plan_t &pl, const void *Q, const void *K,
                        (const TI *)K, (const TI *)V, (TO *)O, pl.d_ctx_idx, pl.d_ctx_len,         \
                        d.clip_len, d.spatial, d.heads, d.head_dim, pl.lk_max, pl.scale,           \
                        ctx_mode ? 1 : 0, (int)pl.global_idx.size(), d.bias_local, d.bias_global,    \
-                       pl.window)
+                       pl.window, (d.flags & DSATTN_FLAG_DEDUP_GLOBAL) ? 1 : 0)
     if (d.io_dtype == DSATTN_F32)
         DSATTN_LAUNCH_GENERIC(float, float);
     else if (d.out_dtype == DSATTN_F32)

@@ -23,7 +23,8 @@
 // 0/1 selector matrix, which is exact.
 // Options of the scopes: the biases of the two scopes' logits enter as one shift of the raw global
 // scores (a softmax sees only their difference); a sliding window |key frame - query frame| <= r
-// on the local scope is a per-lane mask on the local scores.
+// on the local scope is a per-lane mask on the local scores; the set-union option drops, per
+// query, the global keys whose frame that query already sees.
 //
 // LDS regions are private to a wavefront; the barrier orders nothing, it only paces.
 #pragma once
@@ -52,6 +53,8 @@ struct MfmaArgs {
     float sc;     // scale * log2(e), > 0
     float gshift; // (bias_global - bias_local) / scale: the scope biases as a shift of the raw
                   // global scores (the softmax only sees the difference of the two biases)
+    int32_t dedup;   // set union: drop a global entry whose frame the query already sees
+    uint64_t gdup;   // bit j: global entry j repeats an earlier global entry
 };
 
 struct MfmaVariant {
@@ -302,6 +305,13 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
             }
     }
 
+    // set union only (variants with one global key tile: the four-tile variants have no
+    // registers to spare and the planner does not pick them with that option): lane j keeps
+    // the frame of global entry j
+    constexpr bool kDedup = NGT == 1;
+    int gown = -1;
+    if (kDedup && a.dedup && lane < a.G) gown = a.gidx[lane];
+
     int s_bulk = (16 * c0 + 2 * w) % R;  // ring slot of the bulk tile's first row
     int b0 = (16 * c0) % R;              // ring slot of the window's first frame (16 i - w)
 
@@ -342,6 +352,25 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
             }
         }
 
+        // set union: bit 4 tg + e says that this lane's global key 16 tg + 4 lg + e is dropped for
+        // its query (frame 16 i + l16): it repeats an earlier global entry, or its frame is a
+        // visible local key of that query
+        uint32_t ghid = 0;
+        if (kDedup && a.dedup) {
+            const int lo = max(0, 16 * i - w), hi = min(F, 16 * i + 16 + w);
+            const int aq = 16 * i + l16;
+#pragma unroll
+            for (int tg = 0; tg < NGT; ++tg)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int jk = 16 * tg + 4 * lg + e;
+                    const int gf = __shfl(gown, jk);
+                    bool hid = (a.gdup >> jk) & 1;
+                    hid = hid || (gf >= lo && gf < hi && (a.window < 0 || abs(gf - aq) <= a.window));
+                    ghid |= (uint32_t)hid << (4 * tg + e);
+                }
+        }
+
 #pragma unroll
         for (int hh = 0; hh < HPW; ++hh) {
             // ---- S^T = K Q^T for all key tiles
@@ -375,6 +404,7 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
                     float x = s[tg][e];
                     if (a.gshift != 0.f) x += a.gshift;
                     if (!g_full && !(16 * tg + 4 * lg + e < a.G)) x = -INFINITY;
+                    if (kDedup && a.dedup && ((ghid >> (4 * tg + e)) & 1)) x = -INFINITY;
                     s[tg][e] = x;
                     mx = fmaxf(mx, x);
                 }

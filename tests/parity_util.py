@@ -40,7 +40,7 @@ def library_forward(q, k, v, clip_len, n_clips, w, heads, gidx, out_dtype=None, 
 
 
 def oracle_forward(q, k, v, clip_len, n_clips, w, heads, gidx, scale=0.0, positions=None,
-                   bias_local=0.0, bias_global=0.0, window=None):
+                   bias_local=0.0, bias_global=0.0, window=None, dedup=False):
     """Oracle on the exact upcast of the same tensors; optionally on a subset of positions.
     Returns O as [F, P', C] float64."""
     if positions is not None:
@@ -49,7 +49,7 @@ def oracle_forward(q, k, v, clip_len, n_clips, w, heads, gidx, scale=0.0, positi
     qn, kn, vn = (synth.to_f64_numpy(t, heads) for t in (q, k, v))
     o = oracle.forward(qn, kn, vn, clip_len, n_clips, w, gidx, scale=scale,
                        bias_local=bias_local, bias_global=bias_global,
-                       window=-1 if window is None else window)
+                       window=-1 if window is None else window, dedup=dedup)
     return o.reshape(o.shape[0], o.shape[1], -1)
 
 

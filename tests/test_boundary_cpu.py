@@ -220,6 +220,20 @@ def test_planner_fallbacks_and_overrides(monkeypatch):
         plan.close()
 
 
+def test_flags_are_validated_and_dedup_limits_the_planner():
+    lib = B.load()
+    d = B.DsattnDesc(16, 4, 2, 4, 2, 160, B.DSATTN_BF16, B.DSATTN_BF16, 0.0, 8, 0.0, 0.0, 0)
+    out = ctypes.c_void_p()
+    assert lib.dsattn_plan(ctypes.byref(d), None, 0, -1, ctypes.byref(out)) == B.DSATTN_EINVAL
+    assert "flag" in B.dsattn_last_error()
+    # the set-union option runs on the matrix-core kernel with up to 16 global frames
+    for G, kernel in ((16, 1), (17, 0), (0, 1)):
+        plan = B.dsattn_plan(16, 8, 2, 4, 2, 160, list(range(G)), flags=B.DSATTN_FLAG_DEDUP_GLOBAL,
+                             device=-1)
+        assert B.dsattn_plan_launch_info(plan)["kernel"] == kernel
+        plan.close()
+
+
 @pytest.mark.parametrize("D,h,G,hpw", [
     (128, 8, 16, 1), (96, 8, 16, 2), (96, 5, 16, 1), (64, 8, 16, 2), (64, 3, 0, 1), (32, 8, 16, 4),
     (32, 6, 16, 2), (32, 7, 3, 1), (40, 6, 16, 2), (40, 5, 16, 1), (80, 3, 16, 1),

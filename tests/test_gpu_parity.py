@@ -504,3 +504,50 @@ def test_randomised_shapes_against_oracle():
         expect_mfma = clip_len == 16 and D != 24 and (w <= 16 if G <= 16 else w <= 8)
         assert info["kernel"] == (1 if expect_mfma else 0), (info, case)
         U.assert_parity(o, ref, "f32", what=f"random case {case}")
+
+
+# ---------------------------------------------------------------- set union of the two scopes (Section 4.2)
+
+@pytest.mark.parametrize("w,window,g", [
+    (2, None, [0, 20, 20, 47, 33, 0]),          # repeats inside G, entries inside several clips' ranges
+    (8, None, list(range(0, 64, 4))),           # the paper's sizes: every clip holds some global frames
+    (4, 2, [5, 17, 18, 40, 63]),                # per query under the sliding window
+    (0, None, [3]),
+    (2, 0, list(range(16))),                    # window of the query frame only
+])
+def test_dedup_global_both_kernels(w, window, g):
+    clip_len, n_clips, P, h, D = 16, 4, 3, 2, 160
+    F = clip_len * n_clips
+    q, k, v = make(F, P, h * D, 88, "iid", "bf16")
+    ref = U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g, window=window, dedup=True)
+    cat = U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g, window=window)
+    assert np.abs(ref - cat).max() > 1e-2        # the option matters on these inputs
+    for flags, kernel in ((B.DSATTN_FLAG_DEDUP_GLOBAL, 1),
+                          (B.DSATTN_FLAG_DEDUP_GLOBAL | B.DSATTN_FLAG_FORCE_GENERIC, 0)):
+        announce(f"dedup w={w} window={window} G={len(g)} kernel={kernel}")
+        o, info = U.library_forward(q, k, v, clip_len, n_clips, w, h, g, out_dtype="f32", flags=flags,
+                                    window=window)
+        assert info["kernel"] == kernel
+        U.assert_parity(o, ref, "f32", what=f"dedup kernel {kernel}")
+
+
+def test_dedup_global_other_shapes():
+    # fp32 tensors (generic kernel), head_dim 40 with four heads per wavefront, and more than 16
+    # global frames (the option then runs on the generic kernel)
+    q, k, v = make(12, 2, 16, 89, "iid", "f32")
+    g = [1, 1, 7, 11]
+    ref = U.oracle_forward(q, k, v, 4, 3, 1, 2, g, dedup=True)
+    o, _ = U.library_forward(q, k, v, 4, 3, 1, 2, g, flags=B.DSATTN_FLAG_DEDUP_GLOBAL)
+    U.assert_parity(o, ref, "f32_strict", what="dedup fp32")
+    q, k, v = make(48, 3, 8 * 40, 90, "iid", "bf16")
+    g = [0, 9, 9, 30, 47]
+    ref = U.oracle_forward(q, k, v, 16, 3, 3, 8, g, dedup=True, bias_global=0.7)
+    o, info = U.library_forward(q, k, v, 16, 3, 3, 8, g, out_dtype="f32", flags=B.DSATTN_FLAG_DEDUP_GLOBAL,
+                                bias_global=0.7)
+    assert info["kernel"] == 1 and info["heads_per_wave"] == 4
+    U.assert_parity(o, ref, "f32", what="dedup D=40")
+    g = sorted(set(range(0, 48, 2)))  # 24 global frames
+    ref = U.oracle_forward(q, k, v, 16, 3, 3, 8, g, dedup=True)
+    o, info = U.library_forward(q, k, v, 16, 3, 3, 8, g, out_dtype="f32", flags=B.DSATTN_FLAG_DEDUP_GLOBAL)
+    assert info["kernel"] == 0
+    U.assert_parity(o, ref, "f32", what="dedup G=24")
