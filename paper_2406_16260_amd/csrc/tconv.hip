@@ -179,8 +179,7 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
     // The loop below is scheduled by hand (sched_barrier pins the order): with one wavefront
     // per SIMD nothing else hides latency, so every sub-step's multiplies are interleaved with
     // the LDS reads of the next sub-step's fragments (also across the barrier between stages)
-    // and, in the first half of a stage, with the issue of the next stage's loads (a wavefront
-    // that issues them back to back sits in the memory pipeline's queue meanwhile).
+    // and with the issue of the next stage's loads.
     bf16x8 af[2][MI], bfr[2][NJ];
     constexpr int NR = MI + NJ, NM = MI * NJ;
     constexpr int NKK = kBK / 16;
