@@ -9,9 +9,10 @@
 // along the contraction.  It is a dense contraction (2 * taps * c_in flop per output element
 // against 2 + 2 bytes): bound by the matrix cores, not by HBM.
 //
-// MFMA kernel.  A workgroup of 4 wavefronts (one per SIMD, 512 registers each) computes a
-// (64 MI) x (64 NJ) tile of Y; wavefront (wm, wn) owns a (32 MI) x (32 NJ) quarter as MI x NJ
-// accumulators of v_mfma_f32_32x32x16_bf16 (W rows as the A operand, X rows as the B operand).
+// MFMA kernel.  A workgroup of WVM x WVN wavefronts (4: one per SIMD with 512 registers each; 8:
+// two per SIMD) computes a (32 MI WVM) x (32 NJ WVN) tile of Y; wavefront (wm, wn) owns a
+// (32 MI) x (32 NJ) part as MI x NJ accumulators of v_mfma_f32_32x32x16_bf16 (W rows as the A
+// operand, X rows as the B operand).
 // The contraction runs in stages of 64 channels of one tap, taps innermost.  A stage's X rows
 // and W rows (one 128-byte cache line each) go from global memory straight into LDS with
 // buffer_load ... lds, into one of two slots, while the other slot is multiplied out; one
@@ -26,6 +27,7 @@
 #include <stdint.h>
 
 #include <algorithm>
+#include <cstdlib>
 #include <mutex>
 
 #include "dsattn.h"
@@ -44,6 +46,18 @@ constexpr int kBK = 64;       // contraction depth per stage (bf16 elements)
 constexpr int kRow = 128;     // bytes of one LDS row: the 64 channels of a stage = one cache line
 constexpr int kSlots = 2;     // LDS ring: one stage in use, one on its way
 constexpr int kXcds = 8;
+constexpr int kLdsMax = 160 * 1024;  // LDS of a compute unit, and the cap for one workgroup
+
+// The bf16 epilogue stages a wavefront's rows in LDS, `stage_blocks` 32-row blocks at a time: as
+// many of its MI blocks as fit beside the other wavefronts' (and the bias) in the LDS.
+__host__ __device__ constexpr int stage_row_bytes(int NJ) { return 64 * NJ + 8; }
+__host__ __device__ constexpr int stage_blocks(int MI, int NJ, int NW)
+{
+    int ib = MI;
+    while (ib > 1 && (MI % ib != 0 || NW * 32 * ib * stage_row_bytes(NJ) + NW * 32 * NJ * 4 > kLdsMax))
+        --ib;
+    return ib;
+}
 
 constexpr int kMaxGroups = 4;  // weight sets applied to the same input in one launch
 
@@ -63,11 +77,16 @@ struct ConvArgs {
     int32_t w_bytes;           // taps * c_out * c_in * 2
 };
 
-template <int MI, int NJ, bool OUT_F32>
-__global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
+// MI x NJ accumulator blocks per wavefront, WVM x WVN wavefronts per workgroup (4: one per SIMD
+// with 512 registers each; 8: two per SIMD with 256 each, which lets the hardware fill one
+// wavefront's stalls with the other's matrix instructions)
+template <int MI, int NJ, int WVM, int WVN, bool OUT_F32>
+__global__ __launch_bounds__(64 * WVM * WVN, WVM * WVN / 4) void tconv_mfma_kernel(const ConvArgs a)
 {
-    constexpr int BM = 64 * MI, BN = 64 * NJ;
-    constexpr int GA = BM / 32, GB = BN / 32;  // 8-row groups (one load instruction) per wavefront
+    constexpr int NW = WVM * WVN;
+    constexpr int BM = 32 * MI * WVM, BN = 32 * NJ * WVN;
+    constexpr int GA = BM / 8 / NW, GB = BN / 8 / NW;  // 8-row groups (one load instruction) per wavefront
+    static_assert(GA * 8 * NW == BM && GB * 8 * NW == BN, "the wavefronts share the loads evenly");
     constexpr int ABYTES = BM * kRow, BUF = (BM + BN) * kRow;  // one ring slot
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
@@ -88,7 +107,7 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
 
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wm = wv >> 1, wn = wv & 1;
+    const int wm = wv / WVN, wn = wv - wm * WVN;
 
     // Global -> LDS without passing through registers: one buffer_load ... lds instruction moves
     // 8 rows x 128 B (whole cache lines: half lines cost the memory pipeline the same cycles);
@@ -235,7 +254,7 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
         // the bias of this wavefront's 32 NJ channels goes into LDS now (zeros where there is
         // no bias or no channel), behind everything the loop touches: the stores of the
         // epilogue then depend on no global load
-        constexpr int kStageBytes = 4 * 32 * MI * (64 * NJ + 8);
+        constexpr int kStageBytes = NW * 32 * stage_blocks(MI, NJ, NW) * stage_row_bytes(NJ);
         constexpr int kBiasOff = (kSlots * BUF > kStageBytes) ? kSlots * BUF : kStageBytes;
         float *bw = (float *)(smem + kBiasOff) + wv * (32 * NJ);
         const int cb = n0 + wn * 32 * NJ;
@@ -278,9 +297,10 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
 
     // epilogue: accumulator element e of lane l is output channel 8 (e / 4) + 4 (l / 32) + e % 4
     // and row l % 32 of its block: four consecutive channels per lane and e / 4.
-    constexpr int SROW = 64 * NJ + 8;
-    constexpr int STAGE = 32 * MI * SROW;
-    constexpr int BIAS_OFF = (kSlots * BUF > 4 * STAGE) ? kSlots * BUF : 4 * STAGE;
+    constexpr int SROW = stage_row_bytes(NJ);
+    constexpr int IB = stage_blocks(MI, NJ, NW);
+    constexpr int STAGE = 32 * IB * SROW;
+    constexpr int BIAS_OFF = (kSlots * BUF > NW * STAGE) ? kSlots * BUF : NW * STAGE;
     const int cbase = n0 + wn * 32 * NJ;     // first channel of this wavefront's part
     const int64_t mrow0 = m0 + wm * 32 * MI;  // first row of this wavefront's part
     const float *bl = (const float *)(smem + BIAS_OFF) + wv * (32 * NJ);  // written in the prologue
@@ -288,38 +308,46 @@ __global__ __launch_bounds__(256, 1) void tconv_mfma_kernel(const ConvArgs a)
     if constexpr (!OUT_F32) {
         if ((a.Cout & 7) == 0) {
             // bf16 rows made of whole 16-byte pieces: the wavefront's (32 MI) x (32 NJ) part goes
-            // through its own LDS region (the loop's last barrier has retired every load and
-            // every read of the operand buffers that matters) and leaves as full rows: each
-            // store instruction writes 64 NJ contiguous bytes per row.  Rows are padded by 8
-            // bytes so that the 8-byte writes of 32 consecutive rows spread over the banks.
+            // through its own LDS region, IB 32-row blocks at a time (the loop's last barrier
+            // has retired every load and every read of the operand buffers that matters), and
+            // leaves as full rows: each store instruction writes 64 NJ contiguous bytes per
+            // row.  Rows are padded by 8 bytes so that the 8-byte writes of 32 consecutive rows
+            // spread over the banks.
             constexpr int CPR = 4 * NJ;  // 16-byte pieces per row
             unsigned char *stg = smem + wv * STAGE;
 #pragma unroll
-            for (int j = 0; j < NJ; ++j)
+            for (int i0 = 0; i0 < MI; i0 += IB) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int cl = 32 * j + 8 * g + 4 * (lane >> 5);  // channel within the part
-                    const f32x4 b = *(const f32x4 *)(bl + cl);
+                for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                    for (int i = 0; i < MI; ++i) {
-                        bf16x4 yb;
+                    for (int g = 0; g < 4; ++g) {
+                        const int cl = 32 * j + 8 * g + 4 * (lane >> 5);  // channel within the part
+                        const f32x4 b = *(const f32x4 *)(bl + cl);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) yb[e] = (__bf16)(acc[i][j][4 * g + e] + b[e]);
-                        *(bf16x4 *)(stg + (32 * i + (lane & 31)) * SROW + cl * 2) = yb;
+                        for (int ii = 0; ii < IB; ++ii) {
+                            bf16x4 yb;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                yb[e] = (__bf16)(acc[i0 + ii][j][4 * g + e] + b[e]);
+                            *(bf16x4 *)(stg + (32 * ii + (lane & 31)) * SROW + cl * 2) = yb;
+                        }
+                    }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int it = 0; it < (32 * IB * CPR + 63) / 64; ++it) {
+                    const int q = lane + 64 * it;
+                    const int row = q / CPR, pc = q - row * CPR;
+                    const int64_t m = mrow0 + 32 * i0 + row;
+                    if (q < 32 * IB * CPR && m < a.M && cbase + pc * 8 < a.Cout) {
+                        const uint2 lo = *(const uint2 *)(stg + row * SROW + pc * 16);
+                        const uint2 hi = *(const uint2 *)(stg + row * SROW + pc * 16 + 8);
+                        *(uint4 *)((__bf16 *)gY + m * a.Cout + cbase + pc * 8) =
+                            make_uint4(lo.x, lo.y, hi.x, hi.y);
                     }
                 }
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int it = 0; it < (32 * MI * CPR + 63) / 64; ++it) {
-                const int q = lane + 64 * it;
-                const int row = q / CPR, pc = q - row * CPR;
-                if (q < 32 * MI * CPR && mrow0 + row < a.M && cbase + pc * 8 < a.Cout) {
-                    const uint2 lo = *(const uint2 *)(stg + row * SROW + pc * 16);
-                    const uint2 hi = *(const uint2 *)(stg + row * SROW + pc * 16 + 8);
-                    *(uint4 *)((__bf16 *)gY + (mrow0 + row) * a.Cout + cbase + pc * 8) =
-                        make_uint4(lo.x, lo.y, hi.x, hi.y);
-                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
             }
             return;
         }
@@ -385,12 +413,21 @@ __global__ __launch_bounds__(256) void tconv_generic_kernel(const Tin *X, const 
 }
 
 struct ConvVariant {
-    int MI, NJ;
-    const void *fn[2];  // bf16 / fp32 output
+    int MI, NJ, WVM, WVN;  // tile = (32 MI WVM) x (32 NJ WVN), WVM x WVN wavefronts
+    const void *fn[2];     // bf16 / fp32 output
+    int bm() const { return 32 * MI * WVM; }
+    int bn() const { return 32 * NJ * WVN; }
+    int waves() const { return WVM * WVN; }
 };
+#define DSATTN_CONV_VARIANT(MI, NJ, WVM, WVN)                                    \
+    {MI, NJ, WVM, WVN,                                                           \
+     {(const void *)&tconv_mfma_kernel<MI, NJ, WVM, WVN, false>,                 \
+      (const void *)&tconv_mfma_kernel<MI, NJ, WVM, WVN, true>}}
 const ConvVariant kConvVariants[] = {
-    {4, 4, {(const void *)&tconv_mfma_kernel<4, 4, false>, (const void *)&tconv_mfma_kernel<4, 4, true>}},
-    {3, 5, {(const void *)&tconv_mfma_kernel<3, 5, false>, (const void *)&tconv_mfma_kernel<3, 5, true>}},
+    DSATTN_CONV_VARIANT(4, 4, 2, 2),  // 256 x 256, 4 wavefronts
+    DSATTN_CONV_VARIANT(3, 5, 2, 2),  // 192 x 320, 4 wavefronts
+    DSATTN_CONV_VARIANT(4, 2, 2, 4),  // 256 x 256, 8 wavefronts
+    DSATTN_CONV_VARIANT(2, 5, 4, 2),  // 256 x 320, 8 wavefronts
 };
 
 int conv_validate(const dsattn_conv_desc *d, const char *who)
@@ -424,16 +461,31 @@ const ConvVariant *conv_pick(const dsattn_conv_desc &d, int64_t M, int groups = 
     const int64_t taps = 2 * (int64_t)d.reach + 1;
     if (taps * d.c_out * d.c_in * 2 >= ((int64_t)1 << 31)) return nullptr;
     if ((320 + 2 * (int64_t)d.reach * d.spatial) * d.c_in * 2 >= ((int64_t)1 << 31)) return nullptr;
+    // least multiplied-out area (padding of the last row and column tiles), then the larger
+    // tile (fewer prologues and epilogues), then four wavefronts (measured a little faster than
+    // eight at equal tile size); DSATTN_CONV_WAVES=4|8 restricts the choice for A/B runs
+    int want_waves = 0;
+    if (const char *e = getenv("DSATTN_CONV_WAVES")) {
+        const int w = atoi(e);
+        if (w == 4 || w == 8) want_waves = w;
+    }
     const ConvVariant *best = nullptr;
-    double best_cost = 0;
+    double best_area = 0;
+    int64_t best_tiles = 0;
     for (const ConvVariant &v : kConvVariants) {
-        const int64_t bm = 64 * v.MI, bn = 64 * v.NJ;
+        if (want_waves && v.waves() != want_waves) continue;
+        const int64_t bm = v.bm(), bn = v.bn();
         const int64_t tm = (M + bm - 1) / bm, tn = (d.c_out + bn - 1) / bn;
         if (tm * tn * groups > 0x7fffffffLL / 2) continue;
-        const double cost = (double)(tm * bm) * (double)(tn * bn);  // multiplied-out area
-        if (!best || cost < best_cost) {
+        const double area = (double)(tm * bm) * (double)(tn * bn);
+        const int64_t tiles = tm * tn;
+        const bool better = !best || area < best_area ||
+                            (area == best_area && (tiles < best_tiles ||
+                                                   (tiles == best_tiles && v.waves() < best->waves())));
+        if (better) {
             best = &v;
-            best_cost = cost;
+            best_area = area;
+            best_tiles = tiles;
         }
     }
     return best;
@@ -443,8 +495,9 @@ const ConvVariant *conv_pick(const dsattn_conv_desc &d, int64_t M, int groups = 
 // regions; behind them the bias of each wavefront's 32 NJ channels
 int conv_lds_bytes(const ConvVariant &v)
 {
-    return std::max(kSlots * (64 * v.MI + 64 * v.NJ) * kRow, 4 * 32 * v.MI * (64 * v.NJ + 8)) +
-           4 * 32 * v.NJ * (int)sizeof(float);
+    return std::max(kSlots * (v.bm() + v.bn()) * kRow,
+                    v.waves() * 32 * stage_blocks(v.MI, v.NJ, v.waves()) * stage_row_bytes(v.NJ)) +
+           v.waves() * 32 * v.NJ * (int)sizeof(float);
 }
 
 // A linear layer over M rows is the one-tap case of the convolution (every row its own frame).
@@ -510,14 +563,14 @@ hipError_t conv_launch(const dsattn_conv_desc &d, int64_t M, const ConvVariant *
         a.n = d.reach;
         a.KC = (d.c_in + kBK - 1) / kBK;
         a.KS = (2 * d.reach + 1) * a.KC;
-        const int64_t bm = 64 * v->MI, bn = 64 * v->NJ;
+        const int64_t bm = v->bm(), bn = v->bn();
         a.tiles_n = (int32_t)((d.c_out + bn - 1) / bn);
         a.tiles_m = (int32_t)((M + bm - 1) / bm);
         a.tiles = a.tiles_m * a.tiles_n * groups;
         a.per_xcd = (a.tiles + kXcds - 1) / kXcds;
         a.w_bytes = (int32_t)((2 * (int64_t)d.reach + 1) * d.c_out * d.c_in * 2);
         void *params[] = {&a};
-        return hipLaunchKernel(fn, dim3((unsigned)(a.per_xcd * kXcds)), dim3(256), params,
+        return hipLaunchKernel(fn, dim3((unsigned)(a.per_xcd * kXcds)), dim3(64 * v->waves()), params,
                                (size_t)lds, st);
     }
     const int64_t total = M * d.c_out;
@@ -568,14 +621,14 @@ int dsattn_temporal_conv_info(const dsattn_conv_desc *desc, dsattn_conv_info *in
     *info = dsattn_conv_info{};
     const ConvVariant *v = conv_pick(d, M);
     if (v) {
-        const int64_t bm = 64 * v->MI, bn = 64 * v->NJ;
+        const int64_t bm = v->bm(), bn = v->bn();
         const int64_t tiles = ((M + bm - 1) / bm) * ((d.c_out + bn - 1) / bn);
         info->kernel = 1;
         info->tile_m = (int32_t)bm;
         info->tile_n = (int32_t)bn;
         info->tile_k = kBK;
         info->n_blocks = (int32_t)(((tiles + kXcds - 1) / kXcds) * kXcds);
-        info->block_threads = 256;
+        info->block_threads = 64 * v->waves();
         info->lds_bytes = conv_lds_bytes(*v);
     } else {
         info->kernel = 0;
@@ -628,7 +681,8 @@ int dsattn_linear_info(const dsattn_linear_desc *desc, dsattn_conv_info *info)
     const ConvVariant *v = conv_pick(d, M, desc->n_out);
     info->block_threads = 256;
     if (v) {
-        const int64_t bm = 64 * v->MI, bn = 64 * v->NJ;
+        info->block_threads = 64 * v->waves();
+        const int64_t bm = v->bm(), bn = v->bn();
         const int64_t tiles = ((M + bm - 1) / bm) * ((d.c_out + bn - 1) / bn) * desc->n_out;
         info->kernel = 1;
         info->tile_m = (int32_t)bm;

@@ -64,7 +64,7 @@ def test_conv_info_tiles_and_counts():
     # the headline level's shape: 2,304 frames x 160 positions, 1,280 -> 1,280 channels, 3 taps
     i = B.dsattn_temporal_conv_info(16, 144, 160, 1280, 1280, 1)
     M = 2304 * 160
-    assert i["kernel"] == 1 and i["block_threads"] == 256 and i["tile_k"] == 64
+    assert i["kernel"] == 1 and i["block_threads"] in (256, 512) and i["tile_k"] == 64
     assert 1280 % i["tile_n"] == 0 and M % i["tile_m"] == 0          # no padded area at this shape
     tiles = (M // i["tile_m"]) * (1280 // i["tile_n"])
     assert tiles <= i["n_blocks"] < tiles + 8 and i["n_blocks"] % 8 == 0
