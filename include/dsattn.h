@@ -164,10 +164,13 @@ int dsattn_copy_probe(void *dst, const void *src, int64_t bytes, void *stream);
 /*
  * Clip-parallel group normalisation (Section 4.2, "Group normalization"): the second temporal
  * module of the paper that needs context from every clip.  X is [F, P, C] with F = n_clips *
- * clip_len; the C channels form `groups` contiguous groups.  The statistics of a group are taken
- * over the whole video in the paper's order: per-clip means -> global mean (mean of the clip
- * means) -> per-clip mean squared deviation about the GLOBAL mean -> global variance (mean of
- * those); then  y = (x - mean[g]) / sqrt(var[g] + eps) * gamma[c] + beta[c].
+ * clip_len; the C channels form `groups` contiguous groups.  The statistics of a group are those
+ * of the whole video, which is what the paper's exchange yields (per-clip means -> global mean =
+ * mean of the clip means -> per-clip mean squared deviation about the GLOBAL mean -> global
+ * variance = mean of those); then  y = (x - mean[g]) / sqrt(var[g] + eps) * gamma[c] + beta[c].
+ * Here they are gathered in one pass: every part reports its count, mean and squared deviations
+ * about its own mean, and the parts are merged pairwise (Chan et al.), which gives the same
+ * global mean and (biased) variance.
  */
 typedef struct dsattn_gn_desc {
     int32_t clip_len;  /* F_clip >= 1 */
@@ -180,7 +183,7 @@ typedef struct dsattn_gn_desc {
     float eps;         /* >= 0 */
 } dsattn_gn_desc;
 
-/* Bytes of device workspace dsattn_groupnorm needs for this shape (per-clip partial sums). */
+/* Bytes of device workspace dsattn_groupnorm needs for this shape (per-workgroup moments). */
 int dsattn_groupnorm_workspace(const dsattn_gn_desc *desc, size_t *bytes);
 
 /*
@@ -189,7 +192,7 @@ int dsattn_groupnorm_workspace(const dsattn_gn_desc *desc, size_t *bytes);
  *   stats     : device, [2 * groups] fp32 receiving mean[g] then 1/sqrt(var[g] + eps), or NULL
  *   workspace : device, at least dsattn_groupnorm_workspace() bytes, 16-byte aligned; contents
  *               are overwritten; calls sharing a workspace must not overlap
- * Enqueues five kernels on `stream`; allocates nothing.  Errors: EINVAL, EUNSUPPORTED, EHIP.
+ * Enqueues three kernels on `stream`; allocates nothing.  Errors: EINVAL, EUNSUPPORTED, EHIP.
  */
 int dsattn_groupnorm(const dsattn_gn_desc *desc, const void *X, const float *gamma,
                      const float *beta, void *Y, float *stats, void *workspace,

@@ -1,11 +1,17 @@
 // Clip-parallel group normalisation (Section 4.2, "Group normalization") for one GPU that holds
-// every clip: the statistics of a channel group are those of the whole video, computed in the
-// paper's order (per-clip means -> global mean -> per-clip squared deviations about the global
-// mean -> global variance), then y = (x - mean) * rstd * gamma + beta.
+// every clip: the statistics of a channel group are those of the whole video, then
+// y = (x - mean) * rstd * gamma + beta.  The paper has every device compute its clip's mean,
+// average the means, then compute and average the squared deviations about the global mean: two
+// rounds, because averaging per-clip deviations about per-clip means would be wrong.  The same
+// global mean and variance come out of ONE pass if every part reports (count, mean, sum of squared
+// deviations about its own mean) and the parts are merged with the pairwise update of Chan et
+// al.; that is what is done here (one read of X for the statistics instead of two), and between
+// devices it would be one exchange instead of two.
 //
-// All kernels stream X ([F, P, C], C fastest) with 16-byte lanes; a lane's 16 bytes belong to one
-// group.  Reductions are deterministic: per-thread fp32 sums, a fixed-order sum per workgroup into
-// a partial-sum table in the caller's workspace, and a small finalising kernel in fp64.
+// All kernels stream X ([F, P, C], C fastest) with 16-byte lanes; a lane's 16 bytes belong to at
+// most two groups.  Reductions are deterministic: per-thread fp32 sums about a per-thread pilot,
+// a fixed-order merge per workgroup into a table in the caller's workspace, and a small
+// finalising kernel in fp64.
 #include <hip/hip_bf16.h>
 #include <hip/hip_runtime.h>
 
@@ -65,14 +71,32 @@ __device__ inline void unpack(const uint4 &v, float (&x)[8], float *)
     x[3] = __uint_as_float(v.w);
 }
 
-// Pass 1 (SQDEV = false): per-clip sums.  Pass 2 (SQDEV = true): per-clip sums of squared
-// deviations about the global mean.  blockIdx = (workgroup within clip, clip);
+// Merging two sets of (count, mean, sum of squared deviations about the own mean): the parallel
+// form of Welford's update (Chan et al.), stable whatever the means are.
+struct GnMoments {
+    double n, mean, m2;
+};
+__device__ inline void gn_merge(GnMoments &a, double n, double mean, double m2)
+{
+    if (n <= 0.0) return;
+    const double tot = a.n + n, delta = mean - a.mean;
+    a.mean += delta * (n / tot);
+    a.m2 += m2 + delta * delta * (a.n * n / tot);
+    a.n = tot;
+}
+
+// Statistics pass: one read of X gives, per workgroup and group, the count, the mean and the
+// sum of squared deviations about that mean of the elements the workgroup saw.  Every thread
+// accumulates sum(x - p) and sum((x - p)^2) in fp32 about a pilot p of its own (the first
+// element it reads: same channel, nearby rows, so the sums stay small and nothing cancels),
+// turns them into (count, mean, M2), and one thread per group merges, in a fixed order, the
+// threads that hold the group's channels.  blockIdx = (workgroup within clip, clip);
 // thread (x, y) = (lane of the row, row phase).  A lane's VEC channels lie in group g0 (the
 // first `split` of them) and, when the lane straddles a boundary, in group g0 + 1.
-// partial is [N][bpc][groups].
-template <typename T, bool SQDEV>
-__global__ __launch_bounds__(1024) void gn_partial_kernel(const uint4 *__restrict__ X,
-                                                          const float *__restrict__ mean,
+// Means travel as a pair of floats (pilot or leading part, remainder), so that a mean much
+// larger than the spread loses nothing.  partial is [N][bpc][groups][4].
+template <typename T>
+__global__ __launch_bounds__(1024) void gn_moments_kernel(const uint4 *__restrict__ X,
                                                           float *__restrict__ partial, int ch,
                                                           int cg, int groups,
                                                           int64_t rows_per_clip,
@@ -80,31 +104,39 @@ __global__ __launch_bounds__(1024) void gn_partial_kernel(const uint4 *__restric
 {
     constexpr int VEC = sizeof(T) == 2 ? 8 : 4;
     constexpr int UNR = 4;  // independent row loads in flight per thread
-    extern __shared__ float red[];  // [2][blockDim.y][ch]: sums for g0, then for g0 + 1
+    extern __shared__ float red[];  // [8][blockDim.y][ch]: (count, mean hi, mean lo, M2) for g0, then g0 + 1
     const int lane = threadIdx.x, ry = threadIdx.y, ny = blockDim.y;
     const int clip = blockIdx.y;
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
     const int64_t r1 = min(rows_per_clip, r0 + rows_per_block);
     const int g0 = (lane * VEC) / cg;
     const int split = min(VEC, (g0 + 1) * cg - lane * VEC);
-    const float mu0 = SQDEV ? mean[g0] : 0.f;
-    const float mu1 = SQDEV && split < VEC ? mean[g0 + 1] : 0.f;
-    float acc0 = 0.f, acc1 = 0.f;
     const uint4 *base = X + (int64_t)clip * rows_per_clip * ch + lane;
+    float p0 = 0.f, p1 = 0.f;  // pilots
+    float a0 = 0.f, q0 = 0.f, a1 = 0.f, q1 = 0.f;
+    int rows = 0;
     auto add_row = [&](const uint4 &v) __attribute__((always_inline)) {
         float x[8];
         unpack(v, x, (T *)nullptr);
-        float s0 = 0.f, s1 = 0.f;
+        if (rows == 0) {
+            p0 = x[0];
+            p1 = x[split < VEC ? split : 0];
+        }
+        ++rows;
+        float s0 = 0.f, t0 = 0.f, s1 = 0.f, t1 = 0.f;
 #pragma unroll
         for (int i = 0; i < VEC; ++i) {
             const bool lo = i < split;
-            const float d = x[i] - (lo ? mu0 : mu1);
-            const float t = SQDEV ? d * d : x[i];
-            s0 += lo ? t : 0.f;
-            s1 += lo ? 0.f : t;
+            const float d = x[i] - (lo ? p0 : p1);
+            s0 += lo ? d : 0.f;
+            t0 += lo ? d * d : 0.f;
+            s1 += lo ? 0.f : d;
+            t1 += lo ? 0.f : d * d;
         }
-        acc0 += s0;
-        acc1 += s1;
+        a0 += s0;
+        q0 += t0;
+        a1 += s1;
+        q1 += t1;
     };
     int64_t r = r0 + ry;
     for (; r + (int64_t)(UNR - 1) * ny < r1; r += (int64_t)UNR * ny) {
@@ -116,53 +148,71 @@ __global__ __launch_bounds__(1024) void gn_partial_kernel(const uint4 *__restric
     }
     for (; r < r1; r += ny) add_row(base[r * ch]);
 
-    float *red0 = red, *red1 = red + ny * ch;
-    red0[ry * ch + lane] = acc0;
-    red1[ry * ch + lane] = acc1;
+    const int t = ry * ch + lane, nt = ny * ch;
+    const float c0 = (float)rows * (float)split, c1 = (float)rows * (float)(VEC - split);
+    red[0 * nt + t] = c0;
+    red[1 * nt + t] = p0;
+    red[2 * nt + t] = c0 > 0.f ? a0 / c0 : 0.f;
+    red[3 * nt + t] = c0 > 0.f ? q0 - a0 * a0 / c0 : 0.f;
+    red[4 * nt + t] = c1;
+    red[5 * nt + t] = p1;
+    red[6 * nt + t] = c1 > 0.f ? a1 / c1 : 0.f;
+    red[7 * nt + t] = c1 > 0.f ? q1 - a1 * a1 / c1 : 0.f;
     __syncthreads();
-    // one thread per group adds, in a fixed order, the lanes that hold its channels
-    const int t = ry * ch + lane;
+    // one thread per group merges, in a fixed order, the lanes that hold its channels
     if (t < groups) {
         const int g = t;
         const int l0 = (g * cg) / VEC, l1 = ((g + 1) * cg - 1) / VEC;
-        float s = 0.f;
+        GnMoments m = {0.0, 0.0, 0.0};
         for (int y = 0; y < ny; ++y)
             for (int l = l0; l <= l1; ++l) {
-                const int lg0 = (l * VEC) / cg;
-                if (lg0 == g) s += red0[y * ch + l];
-                if (lg0 == g - 1) s += red1[y * ch + l];
+                const int lg0 = (l * VEC) / cg, e = y * ch + l;
+                if (lg0 == g)
+                    gn_merge(m, red[0 * nt + e], (double)red[1 * nt + e] + (double)red[2 * nt + e],
+                             red[3 * nt + e]);
+                if (lg0 == g - 1)
+                    gn_merge(m, red[4 * nt + e], (double)red[5 * nt + e] + (double)red[6 * nt + e],
+                             red[7 * nt + e]);
             }
-        partial[((int64_t)clip * gridDim.x + blockIdx.x) * groups + g] = s;
+        float *out = partial + (((int64_t)clip * gridDim.x + blockIdx.x) * groups + g) * 4;
+        const float hi = (float)m.mean;
+        out[0] = (float)m.n;
+        out[1] = hi;
+        out[2] = (float)(m.mean - (double)hi);
+        out[3] = (float)m.m2;
     }
 }
 
-// One workgroup per group.  MODE 0: stats[g] = mean of the clip means.  MODE 1:
-// stats[groups + g] = 1 / sqrt(mean of the per-clip mean squared deviations + eps).
-// Clips are equally long, so "the mean over clips of (clip sum / clip size)" is taken as the
-// sum of all partials over (clip size x number of clips), in fp64 and in a fixed order.
-template <int MODE>
+// One workgroup per group merges the workgroups' moments in fp64, in a fixed order:
+// stats[g] = mean, stats[groups + g] = 1 / sqrt(M2 / n + eps) (the biased variance).
 __global__ __launch_bounds__(256) void gn_finalize_kernel(const float *__restrict__ partial,
-                                                          float *__restrict__ stats, int n_clips,
-                                                          int bpc, int groups, double n_clip_elems,
-                                                          float eps)
+                                                          float *__restrict__ stats,
+                                                          int64_t n_blocks, int groups, float eps)
 {
-    __shared__ double red[256];
+    __shared__ double rn[256], rm[256], rq[256];
     const int g = blockIdx.x;
-    const int64_t n = (int64_t)n_clips * bpc;
-    double s = 0.0;
-    for (int64_t i = threadIdx.x; i < n; i += 256) s += (double)partial[i * groups + g];
-    red[threadIdx.x] = s;
+    GnMoments m = {0.0, 0.0, 0.0};
+    for (int64_t i = threadIdx.x; i < n_blocks; i += 256) {
+        const float *p = partial + (i * groups + g) * 4;
+        gn_merge(m, p[0], (double)p[1] + (double)p[2], p[3]);
+    }
+    rn[threadIdx.x] = m.n;
+    rm[threadIdx.x] = m.mean;
+    rq[threadIdx.x] = m.m2;
     __syncthreads();
     for (int w = 128; w > 0; w >>= 1) {
-        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        if ((int)threadIdx.x < w) {
+            GnMoments a = {rn[threadIdx.x], rm[threadIdx.x], rq[threadIdx.x]};
+            gn_merge(a, rn[threadIdx.x + w], rm[threadIdx.x + w], rq[threadIdx.x + w]);
+            rn[threadIdx.x] = a.n;
+            rm[threadIdx.x] = a.mean;
+            rq[threadIdx.x] = a.m2;
+        }
         __syncthreads();
     }
     if (threadIdx.x == 0) {
-        const double v = red[0] / n_clip_elems / (double)n_clips;
-        if (MODE == 0)
-            stats[g] = (float)v;
-        else
-            stats[groups + g] = (float)(1.0 / sqrt(v + (double)eps));
+        stats[g] = (float)rm[0];
+        stats[groups + g] = (float)(1.0 / sqrt(rq[0] / rn[0] + (double)eps));
     }
 }
 
@@ -247,8 +297,8 @@ int gn_validate(const dsattn_gn_desc *d, GnShape &s, const char *who)
 
 size_t gn_workspace_bytes(const dsattn_gn_desc &d, const GnShape &s)
 {
-    // partial sums [N][bpc][groups] + statistics [2 * groups] (mean, then 1/sqrt(var + eps))
-    return ((size_t)d.n_clips * s.bpc * d.groups + 2 * (size_t)d.groups) * sizeof(float);
+    // moments [N][bpc][groups][4] + statistics [2 * groups] (mean, then 1/sqrt(var + eps))
+    return (4 * (size_t)d.n_clips * s.bpc * d.groups + 2 * (size_t)d.groups) * sizeof(float);
 }
 
 }  // namespace
@@ -285,28 +335,19 @@ int dsattn_groupnorm(const dsattn_gn_desc *desc, const void *X, const float *gam
 
     hipStream_t st = (hipStream_t)stream;
     float *partial = (float *)workspace;
-    float *wstats = partial + (size_t)d.n_clips * s.bpc * d.groups;
+    float *wstats = partial + 4 * (size_t)d.n_clips * s.bpc * d.groups;
     const dim3 grid(s.bpc, d.n_clips), block(s.ch, s.rpb);
-    const size_t lds = 2 * (size_t)s.ch * s.rpb * sizeof(float);
-    const double n_clip_elems = (double)s.rows_per_clip * (d.channels / d.groups);
+    const size_t lds = 8 * (size_t)s.ch * s.rpb * sizeof(float);
     const int64_t n16 = (int64_t)d.clip_len * d.n_clips * d.spatial * s.ch;
     int64_t ablocks = (n16 + 256 * 8 - 1) / (256 * 8);
     ablocks = std::max<int64_t>(1, std::min<int64_t>(ablocks, 1 << 20));
 
 #define DSATTN_GN_RUN(T)                                                                          \
     do {                                                                                          \
-        hipLaunchKernelGGL((gn_partial_kernel<T, false>), grid, block, lds, st, (const uint4 *)X, \
-                           (const float *)nullptr, partial, s.ch, s.cg, d.groups,                \
-                           s.rows_per_clip, s.rows_per_block);                                    \
-        hipLaunchKernelGGL(gn_finalize_kernel<0>, dim3(d.groups), dim3(256), 0, st, partial,      \
-                           wstats,                                                                \
-                           d.n_clips, s.bpc, d.groups, n_clip_elems, d.eps);                      \
-        hipLaunchKernelGGL((gn_partial_kernel<T, true>), grid, block, lds, st, (const uint4 *)X,  \
-                           (const float *)wstats, partial, s.ch, s.cg, d.groups,                 \
-                           s.rows_per_clip, s.rows_per_block);                                    \
-        hipLaunchKernelGGL(gn_finalize_kernel<1>, dim3(d.groups), dim3(256), 0, st, partial,      \
-                           wstats,                                                                \
-                           d.n_clips, s.bpc, d.groups, n_clip_elems, d.eps);                      \
+        hipLaunchKernelGGL((gn_moments_kernel<T>), grid, block, lds, st, (const uint4 *)X,        \
+                           partial, s.ch, s.cg, d.groups, s.rows_per_clip, s.rows_per_block);     \
+        hipLaunchKernelGGL(gn_finalize_kernel, dim3(d.groups), dim3(256), 0, st, partial, wstats, \
+                           (int64_t)d.n_clips * s.bpc, d.groups, d.eps);                          \
         hipLaunchKernelGGL(gn_apply_kernel<T>, dim3((unsigned)ablocks), dim3(256), 0, st,         \
                            (const uint4 *)X, (uint4 *)Y, (const float *)wstats, gamma, beta,      \
                            s.ch, s.cg, d.groups, n16);                                           \

@@ -149,3 +149,25 @@ def test_groupnorm_full_size_level():
     ref = ((xg[:, pos] - mean[None, None, :, None]) / torch.sqrt(var + 1e-5)[None, None, :, None])
     ref = ref.reshape(wl.F, len(pos), lv.C).cpu().numpy()
     U.assert_parity(y, ref, "bf16", positions=pos, what="groupnorm full size")
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("offset", [100.0, -3000.0])
+def test_groupnorm_large_means_do_not_cancel(offset):
+    """Means far larger than the deviations (fp32 tensors, |mean| / std up to 3,000): the one-pass
+    statistics keep their accuracy because every partial sum is taken about a nearby pilot."""
+    clip_len, n_clips, P, C, groups = 4, 5, 33, 64, 8
+    F = clip_len * n_clips
+    gen = torch.Generator().manual_seed(4)
+    x = (torch.randn(F, P, C, generator=gen) + offset +
+         0.25 * torch.arange(F, dtype=torch.float32)[:, None, None]).to(DEV)
+    ref, mean, var = oracle.groupnorm(x.cpu().double().numpy(), clip_len, n_clips, groups, eps=1e-5)
+    y, stats = run_gn(x, clip_len, n_clips, groups)
+    st = stats.cpu().double().numpy()
+    # the mean is held to fp32 resolution at its own size, the variance to a few 1e-6 relative
+    np.testing.assert_allclose(st[:groups], mean, rtol=2e-7, atol=0)
+    np.testing.assert_allclose(st[groups:], 1.0 / np.sqrt(var + 1e-5), rtol=1e-5, atol=0)
+    # y = (x - mean) * rstd: the subtraction of two fp32 numbers of size |offset| costs up to
+    # one ulp of them, relative to a spread of order one
+    err = np.abs(y.cpu().double().numpy() - ref).max()
+    assert err <= 4 * abs(offset) * 2.0 ** -24 + 1e-5, err
