@@ -74,7 +74,8 @@ static void run_planner(dsattn_plan_t &pl)
     li.heads_per_wave = 1;
     li.clips_per_task = 1;
     li.block_threads = 64;
-    li.n_tasks = 0;  // grid is 3-D (head, position, clip); see launch_generic
+    const int64_t tasks = (int64_t)d.n_clips * d.spatial * d.heads;
+    li.n_tasks = tasks <= 0x7fffffffLL ? (int32_t)tasks : 0;  // 0: too many for one launch
     li.lds_bytes = (int32_t)((pl.lk_max + d.head_dim) * sizeof(float));
 }
 
