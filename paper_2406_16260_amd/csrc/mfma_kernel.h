@@ -16,9 +16,10 @@
 //     the neighbouring clips (c_pre / c_post of Section 4.1) are reused on chip.
 //   * The next clip's Q/K/V rows are in flight in registers while the current clip is computed.
 // Per clip and head:  S^T = K Q^T  (16x16x32 bf16 MFMA, keys on M, the 16 query frames on N),
-// fp32 softmax over keys (maximum: in-lane plus two cross-lane steps; weights exp2 with the scale
-// folded in), P^T rounded to bf16 and fed straight back as the B operand of  O^T = V^T P^T
-// (16x16x16 bf16 MFMA).  The denominator is the sum of the rounded weights, taken by one more MFMA
+// fp32 softmax over keys (maximum: in-lane plus two cross-lane row swaps; weights exp2 with the
+// scale folded in), P^T rounded to bf16 and fed straight back as the B operand of  O^T = V^T P^T
+// (16x16x16 bf16 MFMA per key tile, or 16x16x32 per pair of key tiles when both scopes have an even
+// number of tiles).  The denominator is the sum of the rounded weights, taken by one more MFMA
 // with an all-ones A operand.  V^T operands are made from row-major V rows with an MFMA against a
 // 0/1 selector matrix, which is exact.
 // Options of the scopes: the biases of the two scopes' logits enter as one shift of the raw global
@@ -76,6 +77,26 @@ __device__ __forceinline__ void wave_sync()
 {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
+}
+
+// Maximum over the lanes l, l ^ 16, l ^ 32, l ^ 48 (the four row groups of one MFMA column) with
+// the row-swap instructions of gfx950: no trip through the LDS crossbar.  A swap of x with itself
+// leaves the partner row's value in one of the two results.
+__device__ __forceinline__ float colmax(float x)
+{
+    {
+        const unsigned a = __builtin_bit_cast(unsigned, x);
+        const auto r = __builtin_amdgcn_permlane16_swap(a, a, false, false);
+        const unsigned r0 = r[0], r1 = r[1];
+        x = fmaxf(__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1));
+    }
+    {
+        const unsigned a = __builtin_bit_cast(unsigned, x);
+        const auto r = __builtin_amdgcn_permlane32_swap(a, a, false, false);
+        const unsigned r0 = r[0], r1 = r[1];
+        x = fmaxf(__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1));
+    }
+    return x;
 }
 
 // WPE = wavefronts per SIMD the register budget is sized for (2: 256 VGPRs, 1: 512); a
@@ -191,13 +212,21 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
     };
 
     // A/B operand of the 16x16x32 MFMA: row `row` of an LDS tile, head `hh`, block `kb`;
-    // channels past the head's D are zero
+    // channels past the head's D are zero.  When D is not a multiple of 32 the lanes past the head
+    // read the first 16 bytes of the row's padding instead, which are cleared once below and
+    // never written again (tile stores write the rows' data chunks only).
+    constexpr bool kPadChunk = D % 32 != 0;
+    if constexpr (kPadChunk) {
+        for (int r = lane; r < 2 * R + 16; r += 64)
+            *(uint4 *)(kring + r * RS + SEG * 2) = make_uint4(0, 0, 0, 0);
+        wave_sync();
+    }
     auto read_op32 = [&](const unsigned char *buf, int row, int hh, int kb)
                          __attribute__((always_inline)) -> bf16x8 {
         const int ch = 4 * kb + lg;  // chunk within the head
-        uint4 x = make_uint4(0, 0, 0, 0);
-        if (4 * kb + 3 < DCH || ch < DCH)
-            x = *(const uint4 *)(buf + row * RS + (hh * DCH + ch) * 16);
+        int off = (hh * DCH + ch) * 16;
+        if (!(4 * kb + 3 < DCH) && ch >= DCH) off = SEG * 2;
+        const uint4 x = *(const uint4 *)(buf + row * RS + off);
         return __builtin_bit_cast(bf16x8, x);
     };
 
@@ -209,25 +238,42 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
         for (int e = 0; e < 8; ++e)
             sel[hf][e] = (8 * lg + e == 16 * hf + l16) ? (__bf16)1.0f : (__bf16)0.0f;
 
-    // A operand of the 16x16x16 MFMA that is all ones (row sums of P^T)
-    const s16x4 ones = {0x3F80, 0x3F80, 0x3F80, 0x3F80};
+    // A operands that are all ones (row sums of P^T)
+    bf16x8 ones8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ones8[e] = (__bf16)1.0f;
+    const s16x4 ones = __builtin_bit_cast(s16x4, __builtin_shufflevector(ones8, ones8, 0, 1, 2, 3));
 
-    // V^T operand (A of the 16x16x16 MFMA) for channels 16*(2kb+hf) .. +15 from the V operand
-    // `av` (16 keys x 32 channels): an exact transpose through the matrix core
-    auto vt_from = [&](const bf16x8 av, int hf) __attribute__((always_inline)) -> s16x4 {
+    // V^T operand for channels 16*(2kb+hf) .. +15 from the V operand `av` (16 keys x 32 channels):
+    // an exact transpose through the matrix core.  The lane gets keys 4 lg .. 4 lg + 3 of channel
+    // l16: the A operand of the 16x16x16 MFMA, or one half of the A operand of a 16x16x32 MFMA
+    // over a pair of key tiles.
+    auto vt_from = [&](const bf16x8 av, int hf) __attribute__((always_inline)) -> bf16x4 {
         f32x4 z = {0.f, 0.f, 0.f, 0.f};
         z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, sel[hf], z, 0, 0, 0);
         bf16x4 b;
 #pragma unroll
         for (int e = 0; e < 4; ++e) b[e] = (__bf16)z[e];  // exact: z holds bf16 values
-        return __builtin_bit_cast(s16x4, b);
+        return b;
     };
+    auto join = [](const bf16x4 x, const bf16x4 y) __attribute__((always_inline)) -> bf16x8 {
+        return __builtin_shufflevector(x, y, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+
+    // When both scopes have an even number of key tiles, the tiles enter O^T = V^T P^T in pairs
+    // (32 keys per 16x16x32 MFMA: k-group lg holds keys 4 lg .. 4 lg + 3 of the pair's first tile,
+    // then of its second, in both operands).  Otherwise every tile goes through the 16x16x16 MFMA:
+    // an accumulator chain never mixes the two instructions.
+    constexpr bool kPairs = NGT % 2 == 0 && NLT % 2 == 0;
+    constexpr int NGP = kPairs ? NGT / 2 : 0, NLP = kPairs ? NLT / 2 : 0;  // tile pairs
+    constexpr int NGS = NGT - 2 * NGP, NLS = NLT - 2 * NLP;                // single tiles
 
     // ---- prologue.  Independent loads are issued together so that the chunk starts after
     // two memory round trips: (1) global frame indices, boundary frames, Q of the first clip;
     // (2) global K/V rows, K/V of the first clip.
     bf16x8 kg[NGT > 0 ? NGT : 1][HPW][NKB];
-    s16x4 vgt[NGT > 0 ? NGT : 1][HPW][NDT];
+    bf16x8 vgp[NGP > 0 ? NGP : 1][HPW][NDT];  // V^T of the global tile pairs
+    bf16x4 vgs[NGS > 0 ? NGS : 1][HPW][NDT];  // V^T of the single global tiles
     uint4 stQ[NLD], stK[NLD], stV[NLD];
     uint4 gK[NLD], gV[NLD];
 
@@ -301,9 +347,30 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
                 const bf16x8 av = read_op32(qo, l16, hh, kb);
 #pragma unroll
                 for (int hf = 0; hf < 2; ++hf)
-                    if (2 * kb + hf < NDT) vgt[tg][hh][2 * kb + hf] = vt_from(av, hf);
+                    if (2 * kb + hf < NDT) {
+                        const bf16x4 t = vt_from(av, hf);
+                        if (tg < 2 * NGP) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                vgp[tg / 2][hh][2 * kb + hf][4 * (tg & 1) + e] = t[e];
+                        } else {
+                            vgs[tg - 2 * NGP][hh][2 * kb + hf] = t;
+                        }
+                    }
             }
     }
+
+    // weights of local keys past the ring's R rows are cleared after rounding (their scores
+    // repeat row R - 1, see arow below): masks of this lane's keys 4 lg + e of local tile tl
+    // (R is even, so the two keys of a packed pair are kept or cleared together)
+    bool pkeep[NLT][2];
+#pragma unroll
+    for (int tl = 0; tl < NLT; ++tl)
+#pragma unroll
+        for (int q = 0; q < 2; ++q) pkeep[tl][q] = 16 * tl + 4 * lg + 2 * q < R;
+    // no option and no partly used global tile: interior clips need no per-score masks
+    const bool plain_opts = a.window < 0 && a.gshift == 0.f && a.G == 16 * NGT &&
+                            !(NGT == 1 && a.dedup);
 
     // set union only (variants with one global key tile: the four-tile variants have no
     // registers to spare and the planner does not pick them with that option): lane j keeps
@@ -396,65 +463,124 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
             // scores (scale > 0), weights are exp2(raw * sc - max * sc); masked keys sit at -inf
             // and come out as exact zeros.  The scope bias enters as a shift of the global scores.
             float mx = -INFINITY;
-            const bool g_full = a.G == 16 * NGT;  // no partly used global key tile
+            if (plain_opts && interior) {
+                // every ring row and every global row is a key; rows past R repeat row R - 1, so
+                // they do not change the maximum, and their weights are cleared below
 #pragma unroll
-            for (int tg = 0; tg < NGT; ++tg)
+                for (int tt = 0; tt < NT; ++tt)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float x = s[tg][e];
-                    if (a.gshift != 0.f) x += a.gshift;
-                    if (!g_full && !(16 * tg + 4 * lg + e < a.G)) x = -INFINITY;
-                    if (kDedup && a.dedup && ((ghid >> (4 * tg + e)) & 1)) x = -INFINITY;
-                    s[tg][e] = x;
-                    mx = fmaxf(mx, x);
-                }
+                    for (int e = 0; e < 4; ++e) mx = fmaxf(mx, s[tt][e]);
+            } else {
+                const bool g_full = a.G == 16 * NGT;  // no partly used global key tile
 #pragma unroll
-            for (int tl = 0; tl < NLT; ++tl)
+                for (int tg = 0; tg < NGT; ++tg)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float x = lvalid[tl][e] ? s[NGT + tl][e] : -INFINITY;
-                    s[NGT + tl][e] = x;
-                    mx = fmaxf(mx, x);
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
+                    for (int e = 0; e < 4; ++e) {
+                        float x = s[tg][e];
+                        if (a.gshift != 0.f) x += a.gshift;
+                        if (!g_full && !(16 * tg + 4 * lg + e < a.G)) x = -INFINITY;
+                        if (kDedup && a.dedup && ((ghid >> (4 * tg + e)) & 1)) x = -INFINITY;
+                        s[tg][e] = x;
+                        mx = fmaxf(mx, x);
+                    }
+#pragma unroll
+                for (int tl = 0; tl < NLT; ++tl)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float x = lvalid[tl][e] ? s[NGT + tl][e] : -INFINITY;
+                        s[NGT + tl][e] = x;
+                        mx = fmaxf(mx, x);
+                    }
+            }
+            mx = colmax(mx);
             const float nm = -mx * a.sc;
-            s16x4 pt[NT];
-            // the denominator is the sum of the *rounded* weights, taken on the matrix core:
-            // a row of ones times P^T leaves sum_k P^T[k][a] in every row of column a
-            f32x4 den = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int tt = 0; tt < NT; ++tt) {
+            // rounded weights of key tile tt (this lane: keys 4 lg + e, query l16)
+            auto weights = [&](int tt) __attribute__((always_inline)) -> bf16x4 {
                 bf16x4 pb;
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
                     pb[e] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[tt][e], a.sc, nm));  // RNE
-                pt[tt] = __builtin_bit_cast(s16x4, pb);
-                den = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ones, pt[tt], den, 0, 0, 0);
+                if (tt > NGT) {  // a local tile after the first may reach past the ring
+                    uint2 u = __builtin_bit_cast(uint2, pb);
+                    u.x = pkeep[tt - NGT][0] ? u.x : 0u;
+                    u.y = pkeep[tt - NGT][1] ? u.y : 0u;
+                    pb = __builtin_bit_cast(bf16x4, u);
+                }
+                return pb;
+            };
+            bf16x8 ptp[NGP + NLP > 0 ? NGP + NLP : 1];  // global pairs, then local pairs
+            bf16x4 ptg[NGS > 0 ? NGS : 1], ptl[NLS > 0 ? NLS : 1];  // single tiles
+            // the denominator is the sum of the *rounded* weights, taken on the matrix core:
+            // a row of ones times P^T leaves sum_k P^T[k][a] in every row of column a
+            f32x4 den = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int u = 0; u < NGP; ++u) {
+                ptp[u] = join(weights(2 * u), weights(2 * u + 1));
+                den = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones8, ptp[u], den, 0, 0, 0);
             }
-            const float inv = 1.0f / den[0];
+#pragma unroll
+            for (int u = 0; u < NLP; ++u) {
+                ptp[NGP + u] = join(weights(NGT + 2 * u), weights(NGT + 2 * u + 1));
+                den = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones8, ptp[NGP + u], den, 0, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < NGS; ++u) {
+                ptg[u] = weights(2 * NGP + u);
+                den = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
+                    ones, __builtin_bit_cast(s16x4, ptg[u]), den, 0, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < NLS; ++u) {
+                ptl[u] = weights(NGT + 2 * NLP + u);
+                den = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
+                    ones, __builtin_bit_cast(s16x4, ptl[u]), den, 0, 0, 0);
+            }
+            const float inv = __builtin_amdgcn_rcpf(den[0]);  // within 1 ulp
 
             // ---- O^T = V^T P^T
             f32x4 o[NDT];
 #pragma unroll
             for (int dt = 0; dt < NDT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int tg = 0; tg < NGT; ++tg)
+            for (int u = 0; u < NGP; ++u)
 #pragma unroll
                 for (int dt = 0; dt < NDT; ++dt)
-                    o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vgt[tg][hh][dt], pt[tg], o[dt],
-                                                                     0, 0, 0);
+                    o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vgp[u][hh][dt], ptp[u], o[dt], 0,
+                                                                    0, 0);
 #pragma unroll
-            for (int tl = 0; tl < NLT; ++tl)
+            for (int u = 0; u < NGS; ++u)
+#pragma unroll
+                for (int dt = 0; dt < NDT; ++dt)
+                    o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
+                        __builtin_bit_cast(s16x4, vgs[u][hh][dt]),
+                        __builtin_bit_cast(s16x4, ptg[u]), o[dt], 0, 0, 0);
+#pragma unroll
+            for (int u = 0; u < NLP; ++u)
 #pragma unroll
                 for (int kb = 0; kb < NKB; ++kb) {
-                    const bf16x8 av = read_op32(vring, arow[tl], hh, kb);
+                    const bf16x8 av0 = read_op32(vring, arow[2 * u], hh, kb);
+                    const bf16x8 av1 = read_op32(vring, arow[2 * u + 1], hh, kb);
+#pragma unroll
+                    for (int hf = 0; hf < 2; ++hf) {
+                        const int dt = 2 * kb + hf;
+                        if (dt < NDT)
+                            o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                join(vt_from(av0, hf), vt_from(av1, hf)), ptp[NGP + u], o[dt], 0, 0,
+                                0);
+                    }
+                }
+#pragma unroll
+            for (int u = 0; u < NLS; ++u)
+#pragma unroll
+                for (int kb = 0; kb < NKB; ++kb) {
+                    const bf16x8 av = read_op32(vring, arow[2 * NLP + u], hh, kb);
 #pragma unroll
                     for (int hf = 0; hf < 2; ++hf) {
                         const int dt = 2 * kb + hf;
                         if (dt < NDT)
                             o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
-                                vt_from(av, hf), pt[NGT + tl], o[dt], 0, 0, 0);
+                                __builtin_bit_cast(s16x4, vt_from(av, hf)),
+                                __builtin_bit_cast(s16x4, ptl[u]), o[dt], 0, 0, 0);
                     }
                 }
 
