@@ -99,55 +99,66 @@ template <typename T>
 __global__ __launch_bounds__(1024) void gn_moments_kernel(const uint4 *__restrict__ X,
                                                           float *__restrict__ partial, int ch,
                                                           int cg, int groups,
-                                                          int64_t rows_per_clip,
-                                                          int64_t rows_per_block)
+                                                          int64_t rows_per_clip)
 {
     constexpr int VEC = sizeof(T) == 2 ? 8 : 4;
     constexpr int UNR = 4;  // independent row loads in flight per thread
     extern __shared__ float red[];  // [8][blockDim.y][ch]: (count, mean hi, mean lo, M2) for g0, then g0 + 1
     const int lane = threadIdx.x, ry = threadIdx.y, ny = blockDim.y;
     const int clip = blockIdx.y;
-    const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
-    const int64_t r1 = min(rows_per_clip, r0 + rows_per_block);
     const int g0 = (lane * VEC) / cg;
     const int split = min(VEC, (g0 + 1) * cg - lane * VEC);
     const uint4 *base = X + (int64_t)clip * rows_per_clip * ch + lane;
-    float p0 = 0.f, p1 = 0.f;  // pilots
-    float a0 = 0.f, q0 = 0.f, a1 = 0.f, q1 = 0.f;
+    // Per element slot of the lane: running sums of (x - pilot) and (x - pilot)^2.  The pilot of a
+    // slot is the lane's first element of the slot's group, so every slot of a group is taken about
+    // the same value and the slots' sums add up to the group's; three vector operations per element.
+    float pv[VEC], a[VEC], q[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) pv[i] = a[i] = q[i] = 0.f;
     int rows = 0;
     auto add_row = [&](const uint4 &v) __attribute__((always_inline)) {
         float x[8];
         unpack(v, x, (T *)nullptr);
         if (rows == 0) {
-            p0 = x[0];
-            p1 = x[split < VEC ? split : 0];
+            const float p0 = x[0], p1 = x[split < VEC ? split : 0];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) pv[i] = i < split ? p0 : p1;
         }
         ++rows;
-        float s0 = 0.f, t0 = 0.f, s1 = 0.f, t1 = 0.f;
 #pragma unroll
         for (int i = 0; i < VEC; ++i) {
-            const bool lo = i < split;
-            const float d = x[i] - (lo ? p0 : p1);
-            s0 += lo ? d : 0.f;
-            t0 += lo ? d * d : 0.f;
-            s1 += lo ? 0.f : d;
-            t1 += lo ? 0.f : d * d;
+            const float d = x[i] - pv[i];
+            a[i] += d;
+            q[i] = fmaf(d, d, q[i]);
         }
-        a0 += s0;
-        q0 += t0;
-        a1 += s1;
-        q1 += t1;
     };
-    int64_t r = r0 + ry;
-    for (; r + (int64_t)(UNR - 1) * ny < r1; r += (int64_t)UNR * ny) {
-        uint4 v[UNR];
+    // The workgroups of a clip take its rows in interleaved bites of UNR * ny rows, so that they
+    // sweep the clip together and the chip reads a few long streams instead of one per workgroup.
+    const int64_t bite = (int64_t)UNR * ny;
+    for (int64_t rb = (int64_t)blockIdx.x * bite; rb < rows_per_clip; rb += (int64_t)gridDim.x * bite) {
+        const int64_t r = rb + ry;
+        if (rb + bite <= rows_per_clip) {
+            uint4 v[UNR];
 #pragma unroll
-        for (int u = 0; u < UNR; ++u) v[u] = base[(r + (int64_t)u * ny) * ch];
+            for (int u = 0; u < UNR; ++u) v[u] = base[(r + (int64_t)u * ny) * ch];
 #pragma unroll
-        for (int u = 0; u < UNR; ++u) add_row(v[u]);
+            for (int u = 0; u < UNR; ++u) add_row(v[u]);
+        } else {
+            for (int u = 0; u < UNR; ++u)
+                if (r + (int64_t)u * ny < rows_per_clip) add_row(base[(r + (int64_t)u * ny) * ch]);
+        }
     }
-    for (; r < r1; r += ny) add_row(base[r * ch]);
 
+    float p0 = pv[0], p1 = pv[VEC - 1];
+    float a0 = 0.f, q0 = 0.f, a1 = 0.f, q1 = 0.f;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+        const bool lo = i < split;
+        a0 += lo ? a[i] : 0.f;
+        q0 += lo ? q[i] : 0.f;
+        a1 += lo ? 0.f : a[i];
+        q1 += lo ? 0.f : q[i];
+    }
     const int t = ry * ch + lane, nt = ny * ch;
     const float c0 = (float)rows * (float)split, c1 = (float)rows * (float)(VEC - split);
     red[0 * nt + t] = c0;
@@ -345,7 +356,7 @@ int dsattn_groupnorm(const dsattn_gn_desc *desc, const void *X, const float *gam
 #define DSATTN_GN_RUN(T)                                                                          \
     do {                                                                                          \
         hipLaunchKernelGGL((gn_moments_kernel<T>), grid, block, lds, st, (const uint4 *)X,        \
-                           partial, s.ch, s.cg, d.groups, s.rows_per_clip, s.rows_per_block);     \
+                           partial, s.ch, s.cg, d.groups, s.rows_per_clip);                       \
         hipLaunchKernelGGL(gn_finalize_kernel, dim3(d.groups), dim3(256), 0, st, partial, wstats, \
                            (int64_t)d.n_clips * s.bpc, d.groups, d.eps);                          \
         hipLaunchKernelGGL(gn_apply_kernel<T>, dim3((unsigned)ablocks), dim3(256), 0, st,         \
