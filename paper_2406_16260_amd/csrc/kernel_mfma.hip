@@ -51,8 +51,6 @@ bool mfma_plan(dsattn_plan_t &pl)
     // global key tiles: variants exist for 0, 1 and 4 tiles; a partly used tile is masked
     if (G > 64) return false;
     const int NGT = G == 0 ? 0 : (G <= 16 ? 1 : 4);
-    // the set-union option is built into the variants with one global key tile only
-    if ((d.flags & DSATTN_FLAG_DEDUP_GLOBAL) && NGT == 4) return false;
     const int R = 16 + 2 * d.local_ctx;
     const int NLT = (R + 15) / 16;
     const bool out_f32 = d.out_dtype == DSATTN_F32;
@@ -75,6 +73,9 @@ bool mfma_plan(dsattn_plan_t &pl)
         if (var) break;
     }
     if (!var) return false;
+    // the set-union option is built into the variants with one global key tile, and into the
+    // four-tile variants that run one wavefront per SIMD (head_dim 160 and 128)
+    if ((d.flags & DSATTN_FLAG_DEDUP_GLOBAL) && NGT == 4 && var->WPE != 1) return false;
     const int hpw = var->HPW;
     const int lds_wave = (2 * R + 16) * row_stride_bytes(d.head_dim * hpw);
     if (lds_wave > kLdsPerCu) return false;

@@ -369,13 +369,14 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
 #pragma unroll
         for (int q = 0; q < 2; ++q) pkeep[tl][q] = 16 * tl + 4 * lg + 2 * q < R;
     // no option and no partly used global tile: interior clips need no per-score masks
+    // The set-union option is built into the variants with one global key tile and into the
+    // four-tile variants that have a whole SIMD's registers (the others have none to spare; the
+    // planner does not pick them with that option).
+    constexpr bool kDedup = NGT == 1 || (NGT == 4 && WPE == 1);
     const bool plain_opts = a.window < 0 && a.gshift == 0.f && a.G == 16 * NGT &&
-                            !(NGT == 1 && a.dedup);
+                            !(kDedup && a.dedup);
 
-    // set union only (variants with one global key tile: the four-tile variants have no
-    // registers to spare and the planner does not pick them with that option): lane j keeps
-    // the frame of global entry j
-    constexpr bool kDedup = NGT == 1;
+    // set union: lane j keeps the frame of global entry j
     int gown = -1;
     if (kDedup && a.dedup && lane < a.G) gown = a.gidx[lane];
 

@@ -226,11 +226,13 @@ def test_flags_are_validated_and_dedup_limits_the_planner():
     out = ctypes.c_void_p()
     assert lib.dsattn_plan(ctypes.byref(d), None, 0, -1, ctypes.byref(out)) == B.DSATTN_EINVAL
     assert "flag" in B.dsattn_last_error()
-    # the set-union option runs on the matrix-core kernel with up to 16 global frames
-    for G, kernel in ((16, 1), (17, 0), (0, 1)):
-        plan = B.dsattn_plan(16, 8, 2, 4, 2, 160, list(range(G)), flags=B.DSATTN_FLAG_DEDUP_GLOBAL,
+    # the set-union option runs on the matrix-core kernel with up to 16 global frames, and with
+    # up to 64 where the variant has a whole SIMD's registers (head_dim 160 and 128)
+    for D, G, kernel in ((160, 16, 1), (160, 17, 1), (160, 64, 1), (160, 0, 1), (128, 40, 1),
+                         (80, 16, 1), (80, 17, 0), (40, 64, 0), (96, 33, 0)):
+        plan = B.dsattn_plan(16, 8, 2, 4, 2, D, list(range(G)), flags=B.DSATTN_FLAG_DEDUP_GLOBAL,
                              device=-1)
-        assert B.dsattn_plan_launch_info(plan)["kernel"] == kernel
+        assert B.dsattn_plan_launch_info(plan)["kernel"] == kernel, (D, G)
         plan.close()
 
 

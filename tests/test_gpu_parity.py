@@ -564,3 +564,20 @@ def test_dedup_global_other_shapes():
     o, info = U.library_forward(q, k, v, 16, 3, 3, 8, g, out_dtype="f32", flags=B.DSATTN_FLAG_DEDUP_GLOBAL)
     assert info["kernel"] == 0
     U.assert_parity(o, ref, "f32", what="dedup G=24")
+
+
+@pytest.mark.parametrize("D,h", [(160, 2), (128, 3)])
+@pytest.mark.parametrize("w,window,G", [(4, None, 64), (2, None, 17), (8, 3, 40), (0, None, 33), (4, 0, 64)])
+def test_dedup_global_many_global_frames_on_matrix_cores(D, h, w, window, G):
+    # 17..64 global frames with the set union: head_dim 160 and 128 keep it on the matrix cores
+    # (one wavefront per SIMD); entries repeat each other and lie inside several clips' ranges
+    n_clips = 5
+    rng = np.random.default_rng(100 + G)
+    g = rng.integers(0, 16 * n_clips, size=G).tolist()
+    q, k, v = make(16 * n_clips, 2, h * D, 93, "iid", "bf16")
+    ref = U.oracle_forward(q, k, v, 16, n_clips, w, h, g, window=window, dedup=True, bias_global=-0.3)
+    with planner_env(2, None):
+        o, info = U.library_forward(q, k, v, 16, n_clips, w, h, g, out_dtype="f32", window=window,
+                                    flags=B.DSATTN_FLAG_DEDUP_GLOBAL, bias_global=-0.3)
+    assert info["kernel"] == 1 and info["global_tiles"] == 4
+    U.assert_parity(o, ref, "f32", what=f"dedup D={D} G={G} w={w} window={window}")
