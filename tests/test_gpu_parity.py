@@ -286,14 +286,15 @@ def test_mfma_many_global_frames(D, h, P, w, G):
     assert info["global_tiles"] == 4
 
 
-@pytest.mark.parametrize("w", [1, 3, 5, 6, 7, 8, 9, 11, 13, 16])
-@pytest.mark.parametrize("D,h,G", [(160, 2, 16), (40, 4, 16), (80, 2, 64), (40, 2, 64), (64, 2, 0)])
+@pytest.mark.parametrize("w,D,h,G", [
+    (w, D, h, G)
+    for (D, h, G) in [(160, 2, 16), (40, 4, 16), (80, 2, 64), (40, 2, 64), (64, 2, 0)]
+    for w in [1, 3, 5, 6, 7, 8, 9, 11, 13, 16]
+    if G <= 16 or w <= 8])  # 64 global frames run on the matrix cores with w <= 8 only
 def test_mfma_interior_clips_every_local_width(w, D, h, G):
     # 7 clips of which 5 are interior (for w <= 16): full global key tiles and no options, so the
     # interior clips take the softmax path without per-score masks; ring rows past 16 + 2w are
     # cleared after rounding, per packed pair of keys, in every local key tile after the first
-    if G == 64 and w > 8:
-        pytest.skip("64 global frames run on the matrix cores with w <= 8 only")
     g = synth.random_sorted_global_idx(112, G, seed=11) if G else []
     run_mfma_case(7, w, 2, h, D, g, gen="iid", clips_per_task=4, out_dtypes=("f32",),
                   what=f"interior w={w} D={D} G={G}")
