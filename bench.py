@@ -170,7 +170,24 @@ def main():
     gather_bytes = 2 * int(ctx_len.sum()) * L0["level"].P * L0["level"].C * 2  # read + write
     gather = {"ms_per_tensor": round(gather_ms, 4), "GBps": round(gather_bytes / gather_ms / 1e6, 1),
               "bytes_per_tensor": gather_bytes}
-    del kctx
+    # ---- the two-stage path (the paper's data flow on one GPU: materialise every clip's context,
+    # then attend over it with dsattn_forward_ctx), beside the fused path the headline times
+    vctx = torch.empty_like(kctx)
+    o2 = torch.empty_like(L0["o"])
+    B.dsattn_gather_context(L0["plan"], L0["k"], L0["v"], kctx, vctx, stream)
+    B.dsattn_forward_ctx(L0["plan"], L0["q"], kctx, vctx, o2, stream)
+    g0.record(stream)
+    for _ in range(5):
+        B.dsattn_forward_ctx(L0["plan"], L0["q"], kctx, vctx, o2, stream)
+    g1.record(stream)
+    torch.cuda.synchronize()
+    fctx_ms = g0.elapsed_time(g1) / 5
+    B.dsattn_forward(L0["plan"], L0["q"], L0["k"], L0["v"], L0["o"], stream)
+    torch.cuda.synchronize()
+    gather["forward_ctx_ms"] = round(fctx_ms, 4)
+    gather["two_stage_ms"] = round(2 * gather_ms + fctx_ms, 4)
+    gather["two_stage_equals_fused"] = bool(torch.equal(o2, L0["o"]))
+    del kctx, vctx, o2
     # ---- clip-parallel group normalisation of the same level's tensor (Section 4.2), on its own:
     # two reads and one write of the tensor (one statistics pass + apply)
     lvl = L0["level"]

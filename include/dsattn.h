@@ -149,7 +149,9 @@ int dsattn_forward(const dsattn_plan_t *plan, const void *Q, const void *K, cons
 
 /*
  * Same attention, consuming the materialised context of dsattn_gather_context:
- * clip i attends over Kctx[i][0 .. ctx_len[i]).  Runs the generic kernel.
+ * clip i attends over Kctx[i][0 .. ctx_len[i]).  Runs the kernel the plan chose for
+ * dsattn_forward (the matrix-core kernel takes one clip per work item here, reading the clip's
+ * slab of Kctx / Vctx); the result is identical to dsattn_forward's.
  */
 int dsattn_forward_ctx(const dsattn_plan_t *plan, const void *Q, const void *Kctx, const void *Vctx,
                        void *O, void *stream);

@@ -272,7 +272,7 @@ int dsattn_forward(const dsattn_plan_t *plan, const void *Q, const void *K, cons
     DeviceGuard g(plan->device);
     if (g.err != hipSuccess) return hip_fail(g.err, "dsattn_forward: hipSetDevice");
     hipError_t e = plan->launch.kernel == 1
-                       ? launch_mfma(*plan, Q, K, V, O, (hipStream_t)stream)
+                       ? launch_mfma(*plan, Q, K, V, O, false, (hipStream_t)stream)
                        : launch_generic(*plan, Q, K, V, O, false, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, "dsattn_forward: launch");
     return DSATTN_OK;
@@ -293,12 +293,14 @@ int dsattn_forward_ctx(const dsattn_plan_t *plan, const void *Q, const void *Kct
     const size_t nout = n * dtype_size(plan->desc.out_dtype);
     if (overlaps(O, nout, Q, nin) || overlaps(O, nout, Kctx, nctx) || overlaps(O, nout, Vctx, nctx))
         return fail(DSATTN_EINVAL, "dsattn_forward_ctx: O overlaps an input");
-    if (!generic_supported(*plan))
+    if (plan->launch.kernel != 1 && !generic_supported(*plan))
         return fail(DSATTN_EUNSUPPORTED, "dsattn_forward_ctx: context list or problem too large "
                                          "for the generic kernel");
     DeviceGuard g(plan->device);
     if (g.err != hipSuccess) return hip_fail(g.err, "dsattn_forward_ctx: hipSetDevice");
-    hipError_t e = launch_generic(*plan, Q, Kctx, Vctx, O, true, (hipStream_t)stream);
+    hipError_t e = plan->launch.kernel == 1
+                       ? launch_mfma(*plan, Q, Kctx, Vctx, O, true, (hipStream_t)stream)
+                       : launch_generic(*plan, Q, Kctx, Vctx, O, true, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, "dsattn_forward_ctx: launch");
     return DSATTN_OK;
 }

@@ -161,7 +161,7 @@ hipError_t mfma_prepare(const dsattn_plan_t &pl)
 }
 
 hipError_t launch_mfma(const dsattn_plan_t &pl, const void *Q, const void *K, const void *V,
-                       void *O, hipStream_t st)
+                       void *O, bool ctx_mode, hipStream_t st)
 {
     const dsattn_desc &d = pl.desc;
     const dsattn_launch_info &li = pl.launch;
@@ -183,7 +183,8 @@ hipError_t launch_mfma(const dsattn_plan_t &pl, const void *Q, const void *K, co
     a.G = (int32_t)pl.global_idx.size();
     a.R = 16 + 2 * d.local_ctx;
     a.window = pl.window;
-    a.M = li.clips_per_task;
+    a.M = ctx_mode ? 1 : li.clips_per_task;
+    a.cstride = ctx_mode ? (int64_t)pl.lk_max * d.spatial * pl.C : 0;
     a.RG = d.spatial * (d.heads / li.heads_per_wave);
     a.BPC = a.RG / wpb;
     a.C = pl.C;
@@ -201,7 +202,8 @@ hipError_t launch_mfma(const dsattn_plan_t &pl, const void *Q, const void *K, co
 
     // the grid must be exactly chunks x workgroups-per-chunk, each workgroup wpb whole row groups
     const int NC = (d.n_clips + a.M - 1) / a.M;
-    if (a.RG % wpb != 0 || (int64_t)a.BPC * NC * wpb != (int64_t)li.n_tasks)
+    if (a.RG % wpb != 0 || (!ctx_mode && (int64_t)a.BPC * NC * wpb != (int64_t)li.n_tasks) ||
+        (int64_t)a.BPC * NC > 0x7fffffffLL)
         return hipErrorInvalidValue;
 
     void *params[] = {&a};

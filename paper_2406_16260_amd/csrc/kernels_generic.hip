@@ -3,7 +3,7 @@
 //     index-driven slab copy;
 //   * the generic vector-ALU Dual-scope attention (any dtype, head_dim, clip length), one
 //     wavefront per (clip, position, head); it is the fp32 path and the fallback of the
-//     MFMA kernel, and the only consumer of a materialised context;
+//     MFMA kernel, on the original tensors or on a materialised context;
 //   * a plain copy kernel used as the bandwidth yardstick.
 #include <hip/hip_bf16.h>
 #include <hip/hip_runtime.h>

@@ -56,6 +56,9 @@ struct MfmaArgs {
                   // global scores (the softmax only sees the difference of the two biases)
     int32_t dedup;   // set union: drop a global entry whose frame the query already sees
     uint64_t gdup;   // bit j: global entry j repeats an earlier global entry
+    int64_t cstride; // 0: K and V are [F, P, C].  Otherwise they are materialised contexts
+                     // [N, lk_max, P, C] (clip i: its local frames ascending, then the global
+                     // entries) with cstride = lk_max * P * C elements per clip, and M = 1
 };
 
 struct MfmaVariant {
@@ -142,6 +145,17 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
     const unsigned char *Qb = (const unsigned char *)(a.Q + rowoff);
     const unsigned char *Kb = (const unsigned char *)(a.K + rowoff);
     const unsigned char *Vb = (const unsigned char *)(a.V + rowoff);
+    // Materialised context (one clip per chunk): row j of clip c0's slab is local frame lo + j,
+    // then global entry j - (hi - lo).  Moving the bases so that "frame f" of the slab sits at
+    // f * FSB keeps every local address below as it is; global entry j becomes "frame" hi + j.
+    int gfirst = -1;
+    if (a.cstride != 0) {
+        const int lo = max(0, 16 * c0 - w), hi = min(F, 16 * c0 + 16 + w);
+        const int64_t shift = ((int64_t)c0 * a.cstride - (int64_t)lo * a.FS) * 2;
+        Kb += shift;
+        Vb += shift;
+        gfirst = hi;
+    }
 
     // per-lane load geometry: lane-load `r` covers tile row fq[r], 16-byte chunk cq;
     // voff = byte offset from the tile's first frame row, loff = byte offset in a 16-row LDS tile
@@ -284,7 +298,7 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
         for (int r = 0; r < NLD; ++r) {
             const int j = 16 * tg + fq[r];
             gf[r] = -1;
-            if (in_tile(r) && j < a.G) gf[r] = a.gidx[j];
+            if (in_tile(r) && j < a.G) gf[r] = gfirst >= 0 ? gfirst + j : a.gidx[j];
         }
 #pragma unroll
         for (int r = 0; r < NLD; ++r) {

@@ -47,7 +47,8 @@ hipError_t launch_generic(const dsattn_plan_t &pl, const void *Q, const void *K,
 // shape; when it does, it completes pl.launch.
 bool mfma_plan(dsattn_plan_t &pl);
 hipError_t mfma_prepare(const dsattn_plan_t &pl);  // once per plan, plan's device current
+// ctx_mode: K and V are the materialised contexts [N, lk_max, P, C] (one clip per chunk)
 hipError_t launch_mfma(const dsattn_plan_t &pl, const void *Q, const void *K, const void *V,
-                       void *O, hipStream_t st);
+                       void *O, bool ctx_mode, hipStream_t st);
 
 }  // namespace dsattn

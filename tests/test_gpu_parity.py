@@ -104,6 +104,44 @@ def test_gather_context_bit_exact(shape):
     plan.close()
 
 
+@pytest.mark.parametrize("D,h,P,w,G,opts", [
+    (160, 2, 3, 2, 16, {}),                                   # the headline level's shape
+    (160, 8, 2, 8, 16, {}),                                   # the paper's sizes
+    (40, 8, 3, 4, 64, {}),                                    # four global key tiles, paired tiles
+    (80, 2, 5, 0, 5, {"bias_global": 0.4}),                   # no boundary frames, partial global tile
+    (64, 3, 2, 12, 0, {"window": 5}),                         # three local key tiles, no global part
+    (128, 2, 2, 3, 40, {"flags": B.DSATTN_FLAG_DEDUP_GLOBAL}),  # set union needs the real indices
+])
+def test_forward_ctx_on_matrix_cores(D, h, P, w, G, opts):
+    # the two-stage path of the paper (gather the context, then attend over it) through the MFMA
+    # kernel: one clip per chunk reading its slab of the materialised context; same arithmetic
+    # in the same order as the fused path, so the outputs are identical
+    n_clips = 6
+    F = 16 * n_clips
+    g = np.random.default_rng(77 + G).integers(0, F, size=G).tolist()
+    q, k, v = make(F, P, h * D, 31, "iid", "bf16")
+    for od in ("f32", "bf16"):
+        announce(f"forward_ctx mfma D={D} h={h} P={P} w={w} G={G} {opts} out={od}")
+        with planner_env(4, None):
+            plan = B.dsattn_plan(16, n_clips, w, P, h, D, g, io_dtype=B.DSATTN_BF16,
+                                 out_dtype=U.dt_code(od), device=0, **opts)
+        assert B.dsattn_plan_launch_info(plan)["kernel"] == 1
+        lk = B.dsattn_plan_ctx_max(plan)
+        kc = torch.empty((n_clips, lk, P, h * D), dtype=k.dtype, device=DEV)
+        vc = torch.empty_like(kc)
+        B.dsattn_gather_context(plan, k, v, kc, vc)
+        o1 = torch.full((F, P, h * D), float("nan"), dtype=synth.torch_dtype(od), device=DEV)
+        o2 = torch.full_like(o1, float("nan"))
+        B.dsattn_forward(plan, q, k, v, o1)
+        B.dsattn_forward_ctx(plan, q, kc, vc, o2)
+        torch.cuda.synchronize()
+        assert torch.equal(o1, o2)
+        plan.close()
+    ref = U.oracle_forward(q, k, v, 16, n_clips, w, h, g, window=opts.get("window"),
+                           bias_global=opts.get("bias_global", 0.0), dedup="flags" in opts)
+    U.assert_parity(o2, ref, "bf16", what="forward_ctx mfma")
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_forward_ctx_equals_forward(dtype):
     clip_len, n_clips, w, P, h, D = 8, 4, 3, 11, 2, 16
