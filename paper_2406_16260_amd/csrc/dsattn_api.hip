@@ -159,7 +159,7 @@ int dsattn_plan(const dsattn_desc *desc, const int32_t *global_idx, int32_t n_gl
         if (e == hipSuccess && !pl->global_idx.empty())
             e = hipMemcpy(pl->d_global_idx, pl->global_idx.data(),
                           pl->global_idx.size() * sizeof(int32_t), hipMemcpyHostToDevice);
-        if (e == hipSuccess && pl->launch.kernel == 1) e = mfma_prepare(*pl);
+        if (e == hipSuccess) e = pl->launch.kernel == 1 ? mfma_prepare(*pl) : generic_prepare(*pl);
         (void)hipSetDevice(prev);
         if (e != hipSuccess) {
             int code = e == hipErrorOutOfMemory ? DSATTN_ENOMEM : DSATTN_EHIP;

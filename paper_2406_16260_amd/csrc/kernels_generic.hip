@@ -8,6 +8,8 @@
 #include <hip/hip_bf16.h>
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "plan.h"
 
 namespace dsattn {
@@ -197,6 +199,145 @@ __global__ __launch_bounds__(64) void generic_attn_kernel(
     }
 }
 
+// Orders the LDS accesses of one wavefront's lanes (they execute in issue order; only the
+// compiler has to be kept from moving them).
+__device__ inline void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Same arithmetic, in the same order, with the clip's keys and values staged once in LDS as fp32:
+// one workgroup of up to four wavefronts per (clip, position, head), the wavefronts taking the
+// clip's queries in turn.  The plain kernel above reads every key and value row from memory again
+// for each of the clip's queries; this one is used whenever the rows fit in LDS.
+// Dynamic LDS: float sk[lk_max][KS] (the lanes of the score loop walk keys: KS = D + 4 when rows
+// are whole 16-byte pieces, so that eight consecutive rows cover all banks under 16-byte reads,
+// else D made odd), sv[lk_max][D], then per wavefront sp[lk_max] (scores, then weights) and sq[D]
+// (the query row).  Per-wavefront regions start on 16-byte boundaries when D % 4 == 0.
+template <typename Tin, typename Tout>
+__global__ __launch_bounds__(256) void generic_attn_staged_kernel(
+    const Tin *__restrict__ Q, const Tin *__restrict__ K, const Tin *__restrict__ V,
+    Tout *__restrict__ O, const int32_t *__restrict__ ctx_idx, const int32_t *__restrict__ ctx_len,
+    int clip_len, int P, int h, int D, int lk_max, float scale, int ctx_mode, int n_global,
+    float bias_local, float bias_global, int window, int dedup)
+{
+    extern __shared__ float smem[];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int KS = (D & 3) == 0 ? D + 4 : (D | 1);
+    float *sk = smem;
+    float *sv = sk + (size_t)lk_max * KS;
+    const int Lp = (lk_max + 3) & ~3;
+    float *sp = sv + (size_t)lk_max * D + (size_t)wv * (Lp + D);
+    float *sq = sp + Lp;
+
+    int64_t task = blockIdx.x;
+    const int g = (int)(task % h);
+    task /= h;
+    const int p = (int)(task % P);
+    const int i = (int)(task / P);
+
+    const int64_t C = (int64_t)h * D;
+    const int64_t FS = (int64_t)P * C;  // frame stride in elements
+    const int64_t rowoff = (int64_t)p * C + (int64_t)g * D;
+    const int L = ctx_len[i];
+    const int32_t *ctx = ctx_idx + (int64_t)i * lk_max;
+
+    for (int j = wv; j < L; j += nw) {
+        const int64_t fr = ctx_mode ? (int64_t)i * lk_max + j : (int64_t)ctx[j];
+        const Tin *k = K + fr * FS + rowoff;
+        const Tin *v = V + fr * FS + rowoff;
+        for (int d = lane; d < D; d += 64) {
+            sk[(size_t)j * KS + d] = to_f32(k[d]);
+            sv[(size_t)j * D + d] = to_f32(v[d]);
+        }
+    }
+    __syncthreads();
+
+    for (int a = i * clip_len + wv; a < (i + 1) * clip_len; a += nw) {
+        const Tin *q = Q + (int64_t)a * FS + rowoff;
+        for (int d = lane; d < D; d += 64) sq[d] = to_f32(q[d]);
+        wave_lds_sync();
+
+        float m = -INFINITY;
+        for (int j = lane; j < L; j += 64) {
+            const float *k = sk + (size_t)j * KS;
+            float dot = 0.f;
+            if ((D & 3) == 0) {  // rows of whole 16-byte pieces (KS = D + 4): 16-byte LDS reads
+                for (int d = 0; d < D; d += 4) {
+                    const float4 x = *(const float4 *)(sq + d), y = *(const float4 *)(k + d);
+                    dot = fmaf(x.x, y.x, dot);
+                    dot = fmaf(x.y, y.y, dot);
+                    dot = fmaf(x.z, y.z, dot);
+                    dot = fmaf(x.w, y.w, dot);
+                }
+            } else {
+                for (int d = 0; d < D; ++d) dot = fmaf(sq[d], k[d], dot);
+            }
+            float s = dot * scale + (j < L - n_global ? bias_local : bias_global);
+            if (window >= 0 && j < L - n_global && abs(ctx[j] - a) > window) s = -INFINITY;
+            if (dedup && j >= L - n_global) {
+                const int nl = L - n_global, f = ctx[j];
+                bool seen = nl > 0 && f >= ctx[0] && f <= ctx[nl - 1] &&
+                            (window < 0 || abs(f - a) <= window);
+                for (int jj = nl; jj < j && !seen; ++jj) seen = ctx[jj] == f;
+                if (seen) s = -INFINITY;
+            }
+            sp[j] = s;
+            m = fmaxf(m, s);
+        }
+        m = wave_max(m);
+        float z = 0.f;
+        for (int j = lane; j < L; j += 64) {
+            const float e = expf(sp[j] - m);
+            sp[j] = e;
+            z += e;
+        }
+        z = wave_sum(z);
+        wave_lds_sync();
+
+        const float inv = 1.0f / z;
+        Tout *o = O + (int64_t)a * FS + rowoff;
+        for (int d = lane; d < D; d += 64) {
+            float acc = 0.f;
+            for (int j = 0; j < L; ++j) acc = fmaf(sp[j], sv[(size_t)j * D + d], acc);
+            store_out(o + d, acc * inv);
+        }
+        wave_lds_sync();
+    }
+}
+
+// LDS bytes of the staged kernel with nw wavefronts per workgroup
+static size_t staged_lds_bytes(const dsattn_plan_t &pl, int nw)
+{
+    const size_t D = (size_t)pl.desc.head_dim, L = (size_t)pl.lk_max;
+    const size_t KS = (D & 3) == 0 ? D + 4 : (D | 1);
+    const size_t Lp = (L + 3) & ~(size_t)3;  // per-wavefront score rows padded to 16 bytes
+    return (L * (KS + D) + (size_t)nw * (Lp + D)) * sizeof(float);
+}
+static int staged_waves(const dsattn_plan_t &pl) { return std::min(4, std::max(1, pl.desc.clip_len)); }
+constexpr size_t kGenericLdsMax = 160 * 1024;
+
+template <typename Tin, typename Tout>
+static const void *staged_fn()
+{
+    return (const void *)&generic_attn_staged_kernel<Tin, Tout>;
+}
+static const void *staged_fn_for(const dsattn_desc &d)
+{
+    if (d.io_dtype == DSATTN_F32) return staged_fn<float, float>();
+    if (d.out_dtype == DSATTN_F32) return staged_fn<__hip_bfloat16, float>();
+    return staged_fn<__hip_bfloat16, __hip_bfloat16>();
+}
+
+// Raises the staged kernel's dynamic LDS cap (once per plan, outside the launch path).
+hipError_t generic_prepare(const dsattn_plan_t &pl)
+{
+    if (staged_lds_bytes(pl, staged_waves(pl)) > kGenericLdsMax) return hipSuccess;
+    return hipFuncSetAttribute(staged_fn_for(pl.desc), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)kGenericLdsMax);
+}
+
 // The generic kernel keeps one clip's scores and one query row in LDS (64 KB cap) and
 // numbers its wavefront tasks in 31 bits.
 bool generic_supported(const dsattn_plan_t &pl)
@@ -215,6 +356,25 @@ hipError_t launch_generic(const dsattn_plan_t &pl, const void *Q, const void *K,
     if (tasks > 0x7fffffffLL) return hipErrorInvalidValue;
     const size_t lds = (size_t)(pl.lk_max + d.head_dim) * sizeof(float);
     if (lds > 64 * 1024) return hipErrorInvalidValue;
+    const int nw = staged_waves(pl);
+    const size_t slds = staged_lds_bytes(pl, nw);
+    if (slds <= kGenericLdsMax) {
+        const dim3 sgrid((unsigned)tasks), sblock(64 * nw);
+#define DSATTN_LAUNCH_STAGED(TI, TO)                                                              \
+    hipLaunchKernelGGL((generic_attn_staged_kernel<TI, TO>), sgrid, sblock, slds, st,             \
+                       (const TI *)Q, (const TI *)K, (const TI *)V, (TO *)O, pl.d_ctx_idx,        \
+                       pl.d_ctx_len, d.clip_len, d.spatial, d.heads, d.head_dim, pl.lk_max,       \
+                       pl.scale, ctx_mode ? 1 : 0, (int)pl.global_idx.size(), d.bias_local,       \
+                       d.bias_global, pl.window, (d.flags & DSATTN_FLAG_DEDUP_GLOBAL) ? 1 : 0)
+        if (d.io_dtype == DSATTN_F32)
+            DSATTN_LAUNCH_STAGED(float, float);
+        else if (d.out_dtype == DSATTN_F32)
+            DSATTN_LAUNCH_STAGED(__hip_bfloat16, float);
+        else
+            DSATTN_LAUNCH_STAGED(__hip_bfloat16, __hip_bfloat16);
+#undef DSATTN_LAUNCH_STAGED
+        return hipGetLastError();
+    }
     const dim3 grid((unsigned)tasks), block(64);
 #define DSATTN_LAUNCH_GENERIC(TI, TO)                                                             \
     hipLaunchKernelGGL((generic_attn_kernel<TI, TO>), grid, block, lds, st, (const TI *)Q,        \

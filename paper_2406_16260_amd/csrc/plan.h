@@ -40,6 +40,7 @@ hipError_t launch_copy(void *dst, const void *src, int64_t bytes, hipStream_t st
 // Generic vector-ALU attention. ctx_mode = false: K/V are [F,P,C] and keys are
 // fetched through ctx_idx; true: K/V are [N, lk_max, P, C] and key j of clip i is row j.
 bool generic_supported(const dsattn_plan_t &pl);
+hipError_t generic_prepare(const dsattn_plan_t &pl);  // once per plan, plan's device current
 hipError_t launch_generic(const dsattn_plan_t &pl, const void *Q, const void *K, const void *V,
                           void *O, bool ctx_mode, hipStream_t st);
 
