@@ -51,6 +51,11 @@ GENERIC_SHAPES = [
     (7, 5, 3, 33, 3, 72, [0, 34, 17, 17], "f32"),       # D > 64: lanes stride over channels
     (16, 6, 2, 19, 4, 40, list(range(0, 96, 6)), "bf16"),
     (8, 10, 70, 3, 2, 16, list(range(80)), "bf16"),     # more than 64 keys: lanes stride over keys
+    (2, 5, 1, 2, 2, 30, [9, 0], "f32"),                 # clip shorter than a workgroup's 4 wavefronts
+    (5, 3, 2, 3, 1, 18, [1], "bf16"),                   # head_dim not a multiple of 4: scalar LDS reads
+    # 112 keys x 512 channels do not fit in LDS as fp32: the plain kernel reads them from memory
+    (16, 2, 16, 1, 1, 512, list(range(0, 32, 1)) + list(range(0, 32, 1)), "f32"),
+    (16, 3, 4, 2, 1, 768, list(range(0, 48, 2)), "bf16"),
 ]
 
 
