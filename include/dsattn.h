@@ -201,6 +201,26 @@ int dsattn_groupnorm(const dsattn_gn_desc *desc, const void *X, const float *gam
                      size_t workspace_bytes, void *stream);
 
 /*
+ * dsattn_groupnorm for callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels
+ * and the same result as dsattn_groupnorm; the per-workgroup moments go to a file-scope device
+ * array of dsattn_groupnorm_static_max_bytes() = 4 MiB that every device the library runs on
+ * holds until the process ends.  Runs on the current device.  The call allocates nothing (no
+ * hipMalloc, hipFree or allocating library routine); the first call on a device looks the
+ * array's address up once (make that call outside a graph capture).
+ *   - a shape whose dsattn_groupnorm_workspace() exceeds the array is rejected with
+ *     DSATTN_EUNSUPPORTED before anything is enqueued;
+ *   - every call on a device shares that device's array: calls that overlap in time on one
+ *     device (different streams, or graph replays running concurrently) race; calls on one
+ *     stream are ordered and safe.  Nothing in the array has to start at zero: every entry a
+ *     call reads was written earlier in the same call.
+ * Arguments as for dsattn_groupnorm, without the workspace.  Errors: EINVAL, EUNSUPPORTED, EHIP.
+ */
+size_t dsattn_groupnorm_static_max_bytes(void);
+int dsattn_groupnorm_static(const dsattn_gn_desc *desc, const void *X, const float *gamma,
+                            const float *beta, void *Y, float *stats, void *stream);
+
+/*
  * Clip-parallel temporal convolution (Section 4.2, "Convolution module"): the third temporal
  * module of the paper.  X is [F, P, c_in] with F = n_clips * clip_len; the module convolves
  * along the frame axis only, at every position separately, mixing channels densely:

@@ -31,7 +31,7 @@ EXPORTS = (
     "dsattn_plan_launch_info", "dsattn_gather_context", "dsattn_forward", "dsattn_forward_ctx",
     "dsattn_copy_probe", "dsattn_strerror", "dsattn_last_error", "dsattn_groupnorm_workspace",
     "dsattn_groupnorm", "dsattn_temporal_conv_info", "dsattn_temporal_conv", "dsattn_linear_info",
-    "dsattn_linear",
+    "dsattn_linear", "dsattn_groupnorm_static", "dsattn_groupnorm_static_max_bytes",
 )
 
 
@@ -153,6 +153,10 @@ def load():
     lib.dsattn_groupnorm.restype = ctypes.c_int
     lib.dsattn_groupnorm.argtypes = [ctypes.POINTER(DsattnGnDesc), vp, vp, vp, vp, vp, vp,
                                      ctypes.c_size_t, vp]
+    lib.dsattn_groupnorm_static.restype = ctypes.c_int
+    lib.dsattn_groupnorm_static.argtypes = [ctypes.POINTER(DsattnGnDesc), vp, vp, vp, vp, vp, vp]
+    lib.dsattn_groupnorm_static_max_bytes.restype = ctypes.c_size_t
+    lib.dsattn_groupnorm_static_max_bytes.argtypes = []
     lib.dsattn_strerror.restype = ctypes.c_char_p
     lib.dsattn_strerror.argtypes = [ctypes.c_int]
     lib.dsattn_last_error.restype = ctypes.c_char_p
@@ -308,6 +312,18 @@ def dsattn_groupnorm(clip_len, n_clips, spatial, channels, groups, X, Y, workspa
     _check(load().dsattn_groupnorm(ctypes.byref(desc), _ptr(X), _ptr(gamma), _ptr(beta), _ptr(Y),
                                    _ptr(stats), _ptr(workspace), int(workspace_bytes),
                                    _stream(stream)), "dsattn_groupnorm")
+
+
+def dsattn_groupnorm_static_max_bytes() -> int:
+    return int(load().dsattn_groupnorm_static_max_bytes())
+
+
+def dsattn_groupnorm_static(clip_len, n_clips, spatial, channels, groups, X, Y, gamma=None,
+                            beta=None, stats=None, io_dtype=DSATTN_BF16, eps=1e-5, stream=None):
+    desc = DsattnGnDesc(clip_len, n_clips, spatial, channels, groups, io_dtype, float(eps))
+    _check(load().dsattn_groupnorm_static(ctypes.byref(desc), _ptr(X), _ptr(gamma), _ptr(beta),
+                                          _ptr(Y), _ptr(stats), _stream(stream)),
+           "dsattn_groupnorm_static")
 
 
 def dsattn_temporal_conv_info(clip_len, n_clips, spatial, c_in, c_out, reach,

@@ -17,6 +17,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 
 #include "plan.h"
 
@@ -312,6 +313,70 @@ size_t gn_workspace_bytes(const dsattn_gn_desc &d, const GnShape &s)
     return (4 * (size_t)d.n_clips * s.bpc * d.groups + 2 * (size_t)d.groups) * sizeof(float);
 }
 
+// Enqueues the three kernels (and the copy of the statistics); everything is validated.
+hipError_t gn_enqueue(const dsattn_gn_desc &d, const GnShape &s, const void *X, const float *gamma,
+                      const float *beta, void *Y, float *stats, void *workspace, hipStream_t st)
+{
+    float *partial = (float *)workspace;
+    float *wstats = partial + 4 * (size_t)d.n_clips * s.bpc * d.groups;
+    const dim3 grid(s.bpc, d.n_clips), block(s.ch, s.rpb);
+    const size_t lds = 8 * (size_t)s.ch * s.rpb * sizeof(float);
+    const int64_t n16 = (int64_t)d.clip_len * d.n_clips * d.spatial * s.ch;
+    int64_t ablocks = (n16 + 256 * 8 - 1) / (256 * 8);
+    ablocks = std::max<int64_t>(1, std::min<int64_t>(ablocks, 1 << 20));
+
+#define DSATTN_GN_RUN(T)                                                                          \
+    do {                                                                                          \
+        hipLaunchKernelGGL((gn_moments_kernel<T>), grid, block, lds, st, (const uint4 *)X,        \
+                           partial, s.ch, s.cg, d.groups, s.rows_per_clip);                       \
+        hipLaunchKernelGGL(gn_finalize_kernel, dim3(d.groups), dim3(256), 0, st, partial, wstats, \
+                           (int64_t)d.n_clips * s.bpc, d.groups, d.eps);                          \
+        hipLaunchKernelGGL(gn_apply_kernel<T>, dim3((unsigned)ablocks), dim3(256), 0, st,         \
+                           (const uint4 *)X, (uint4 *)Y, (const float *)wstats, gamma, beta,      \
+                           s.ch, s.cg, d.groups, n16);                                           \
+    } while (0)
+    if (d.io_dtype == DSATTN_BF16)
+        DSATTN_GN_RUN(__hip_bfloat16);
+    else
+        DSATTN_GN_RUN(float);
+#undef DSATTN_GN_RUN
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && stats)
+        e = hipMemcpyAsync(stats, wstats, 2 * (size_t)d.groups * sizeof(float),
+                           hipMemcpyDeviceToDevice, st);
+    return e;
+}
+
+// Scratch of dsattn_groupnorm_static: the per-workgroup moments and the statistics live in a
+// file-scope device array instead of a caller's workspace, so that the entry point allocates
+// nothing.  Every device the library runs on holds its own copy of the array at its own address
+// until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the address it returns for the current device is what the kernels get.
+constexpr size_t kGnStaticBytes = (size_t)4 << 20;
+constexpr int kGnMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kGnStaticBytes];
+
+// Device address of the array on the current device, looked up once per device.
+hipError_t gn_static_scratch(void **out)
+{
+    static std::mutex mu;
+    static void *addr[kGnMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kGnMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        addr[dev] = p;
+    }
+    *out = addr[dev];
+    return hipSuccess;
+}
+
 }  // namespace
 }  // namespace dsattn
 
@@ -343,36 +408,35 @@ int dsattn_groupnorm(const dsattn_gn_desc *desc, const void *X, const float *gam
     if (workspace_bytes < gn_workspace_bytes(d, s))
         return fail(DSATTN_EINVAL, "dsattn_groupnorm: workspace too small (%zu < %zu bytes)",
                     workspace_bytes, gn_workspace_bytes(d, s));
-
-    hipStream_t st = (hipStream_t)stream;
-    float *partial = (float *)workspace;
-    float *wstats = partial + 4 * (size_t)d.n_clips * s.bpc * d.groups;
-    const dim3 grid(s.bpc, d.n_clips), block(s.ch, s.rpb);
-    const size_t lds = 8 * (size_t)s.ch * s.rpb * sizeof(float);
-    const int64_t n16 = (int64_t)d.clip_len * d.n_clips * d.spatial * s.ch;
-    int64_t ablocks = (n16 + 256 * 8 - 1) / (256 * 8);
-    ablocks = std::max<int64_t>(1, std::min<int64_t>(ablocks, 1 << 20));
-
-#define DSATTN_GN_RUN(T)                                                                          \
-    do {                                                                                          \
-        hipLaunchKernelGGL((gn_moments_kernel<T>), grid, block, lds, st, (const uint4 *)X,        \
-                           partial, s.ch, s.cg, d.groups, s.rows_per_clip);                       \
-        hipLaunchKernelGGL(gn_finalize_kernel, dim3(d.groups), dim3(256), 0, st, partial, wstats, \
-                           (int64_t)d.n_clips * s.bpc, d.groups, d.eps);                          \
-        hipLaunchKernelGGL(gn_apply_kernel<T>, dim3((unsigned)ablocks), dim3(256), 0, st,         \
-                           (const uint4 *)X, (uint4 *)Y, (const float *)wstats, gamma, beta,      \
-                           s.ch, s.cg, d.groups, n16);                                           \
-    } while (0)
-    if (d.io_dtype == DSATTN_BF16)
-        DSATTN_GN_RUN(__hip_bfloat16);
-    else
-        DSATTN_GN_RUN(float);
-#undef DSATTN_GN_RUN
-    hipError_t e = hipGetLastError();
-    if (e == hipSuccess && stats)
-        e = hipMemcpyAsync(stats, wstats, 2 * (size_t)d.groups * sizeof(float),
-                           hipMemcpyDeviceToDevice, st);
+    const hipError_t e = gn_enqueue(d, s, X, gamma, beta, Y, stats, workspace, (hipStream_t)stream);
     if (e != hipSuccess) return fail(DSATTN_EHIP, "dsattn_groupnorm: %s", hipGetErrorString(e));
+    return DSATTN_OK;
+}
+
+size_t dsattn_groupnorm_static_max_bytes(void) { return kGnStaticBytes; }
+
+int dsattn_groupnorm_static(const dsattn_gn_desc *desc, const void *X, const float *gamma,
+                            const float *beta, void *Y, float *stats, void *stream)
+{
+    GnShape s;
+    const int rc = gn_validate(desc, s, "dsattn_groupnorm_static");
+    if (rc != DSATTN_OK) return rc;
+    const dsattn_gn_desc &d = *desc;
+    if (!X || !Y) return fail(DSATTN_EINVAL, "dsattn_groupnorm_static: null pointer");
+    if (((uintptr_t)X | (uintptr_t)Y) & 15u)
+        return fail(DSATTN_EINVAL, "dsattn_groupnorm_static: pointers must be 16-byte aligned");
+    const size_t need = gn_workspace_bytes(d, s);
+    if (need > kGnStaticBytes)
+        return fail(DSATTN_EUNSUPPORTED,
+                    "dsattn_groupnorm_static: this shape needs %zu bytes of scratch, the static "
+                    "array holds %zu; use dsattn_groupnorm with a workspace",
+                    need, (size_t)kGnStaticBytes);
+    void *ws = nullptr;
+    hipError_t e = gn_static_scratch(&ws);
+    if (e == hipSuccess)
+        e = gn_enqueue(d, s, X, gamma, beta, Y, stats, ws, (hipStream_t)stream);
+    if (e != hipSuccess)
+        return fail(DSATTN_EHIP, "dsattn_groupnorm_static: %s", hipGetErrorString(e));
     return DSATTN_OK;
 }
 
