@@ -88,13 +88,20 @@ typedef struct dsattn_plan_s dsattn_plan_t; /* opaque; made by dsattn_plan() */
 typedef struct dsattn_launch_info {
     int32_t kernel;          /* 0 = generic vector-ALU kernel, 1 = bf16 MFMA streaming kernel */
     int32_t heads_per_wave;  /* MFMA kernel: heads handled by one wavefront */
-    int32_t local_tiles;     /* MFMA kernel: 16-key tiles covering the local window */
+    int32_t local_tiles;     /* MFMA kernel: 16-key tiles covering the local scope of a query tile */
     int32_t global_tiles;    /* MFMA kernel: 16-key tiles covering the global set */
-    int32_t clips_per_task;  /* consecutive clips walked by one wavefront */
+    int32_t clips_per_task;  /* consecutive 16-frame query tiles walked by one wavefront (whole clips
+                                when clip_len is 16; the generic kernel: 1 clip) */
     int32_t n_tasks;         /* wavefront tasks = grid size */
     int32_t block_threads;   /* threads per workgroup */
     int32_t lds_bytes;       /* LDS bytes per workgroup */
     int64_t algorithmic_bytes; /* Q + K + V read once, O written once */
+    int32_t variant;         /* MFMA kernel: index of the kernel variant in the library's table,
+                                resolved once by dsattn_plan (a launch searches nothing);
+                                -1 for the generic kernel */
+    int32_t ring_reach;      /* MFMA kernel: frames kept on chip beyond a query tile on each side
+                                (local_ctx for 16-frame clips; the window radius or the rest of
+                                the clip's local range for longer clips) */
 } dsattn_launch_info;
 
 /*

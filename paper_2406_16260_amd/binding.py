@@ -87,7 +87,8 @@ class DsattnLaunchInfo(ctypes.Structure):
         ("local_tiles", ctypes.c_int32), ("global_tiles", ctypes.c_int32),
         ("clips_per_task", ctypes.c_int32), ("n_tasks", ctypes.c_int32),
         ("block_threads", ctypes.c_int32), ("lds_bytes", ctypes.c_int32),
-        ("algorithmic_bytes", ctypes.c_int64),
+        ("algorithmic_bytes", ctypes.c_int64), ("variant", ctypes.c_int32),
+        ("ring_reach", ctypes.c_int32),
     ]
 
     def as_dict(self):
@@ -196,13 +197,51 @@ def _stream(stream):
     return int(stream)
 
 
+def _dtype_name(code):
+    return "float32" if code == DSATTN_F32 else "bfloat16"
+
+
+def _check_tensors(who, items, device):
+    """Refuse torch tensors that the kernels would read or write out of bounds: wrong element
+    count, element type or device.  The C ABI takes bare pointers and cannot know any of these.
+    items: (tensor, name, numel, dtype code or None); numel is exact unless given as ("min", n).
+    device: the HIP ordinal the call runs on, "current" for entry points that run on the current
+    device, or None to skip the device check (a host-only plan: the library itself refuses the
+    call).  Sizes and types of all tensors are checked before any device.  Raw addresses (int) and
+    None pass through: they are the C-level tests' business."""
+    import torch
+    tensors = [it for it in items if it[0] is not None and hasattr(it[0], "data_ptr")]
+    for t, name, numel, dtype_code in tensors:
+        if not t.is_contiguous():
+            raise ValueError(f"{who}: {name}: tensor must be contiguous")
+        if isinstance(numel, tuple):
+            if t.numel() < numel[1]:
+                raise ValueError(f"{who}: {name}: {t.numel()} elements, at least {numel[1]} needed")
+        elif t.numel() != numel:
+            raise ValueError(f"{who}: {name}: {t.numel()} elements, {numel} expected")
+        if dtype_code is not None:
+            want = torch.float32 if dtype_code == DSATTN_F32 else torch.bfloat16
+            if t.dtype != want:
+                raise ValueError(f"{who}: {name}: dtype {t.dtype}, {_dtype_name(dtype_code)} expected")
+    if device is None:
+        return
+    for t, name, _, _ in tensors:
+        if t.device.type != "cuda":
+            raise ValueError(f"{who}: {name}: tensor is on {t.device}, device memory expected")
+        dev = torch.cuda.current_device() if device == "current" else device
+        if t.device.index != dev:
+            raise ValueError(f"{who}: {name}: tensor is on {t.device}, the call runs on device {dev}")
+
+
 class Plan:
     """Owns one dsattn_plan_t handle."""
 
-    def __init__(self, handle, desc, n_global):
+    def __init__(self, handle, desc, n_global, device=0):
         self.handle = handle
         self.desc = desc
         self.n_global = n_global
+        self.device = device
+        self._lk_max = None
 
     def close(self):
         if self.handle:
@@ -223,6 +262,25 @@ class Plan:
     def C(self):
         return self.desc.heads * self.desc.head_dim
 
+    @property
+    def lk_max(self):
+        if self._lk_max is None:
+            self._lk_max = dsattn_plan_ctx_max(self)
+        return self._lk_max
+
+    def frames(self, t, name, out=False):
+        """Check item for an [F, P, C] tensor of this plan (Q, K, V or O)."""
+        return (t, name, self.F * self.desc.spatial * self.C,
+                self.desc.out_dtype if out else self.desc.io_dtype)
+
+    def ctx(self, t, name):
+        """Check item for a materialised context [N, lk_max, P, C] of this plan."""
+        return (t, name, self.desc.n_clips * self.lk_max * self.desc.spatial * self.C,
+                self.desc.io_dtype)
+
+    def check(self, who, items):
+        _check_tensors(who, items, self.device if self.device >= 0 else None)
+
 
 def dsattn_plan(clip_len, n_clips, local_ctx, spatial, heads, head_dim, global_idx,
                 io_dtype=DSATTN_BF16, out_dtype=None, scale=0.0, flags=0, device=0,
@@ -239,7 +297,7 @@ def dsattn_plan(clip_len, n_clips, local_ctx, spatial, heads, head_dim, global_i
     rc = lib.dsattn_plan(ctypes.byref(desc), g.ctypes.data if g.size else None, int(g.size),
                          int(device), ctypes.byref(handle))
     _check(rc, "dsattn_plan")
-    return Plan(handle, desc, int(g.size))
+    return Plan(handle, desc, int(g.size), int(device))
 
 
 def dsattn_plan_destroy(plan: Plan):
@@ -269,21 +327,31 @@ def dsattn_plan_launch_info(plan: Plan) -> dict:
 
 
 def dsattn_gather_context(plan: Plan, K, V, Kctx, Vctx, stream=None):
+    plan.check("dsattn_gather_context", [plan.frames(K, "K"), plan.frames(V, "V"),
+                                         plan.ctx(Kctx, "Kctx"), plan.ctx(Vctx, "Vctx")])
     _check(load().dsattn_gather_context(plan.handle, _ptr(K), _ptr(V), _ptr(Kctx), _ptr(Vctx),
                                         _stream(stream)), "dsattn_gather_context")
 
 
 def dsattn_forward(plan: Plan, Q, K, V, O, stream=None):
+    plan.check("dsattn_forward", [plan.frames(Q, "Q"), plan.frames(K, "K"), plan.frames(V, "V"),
+                                  plan.frames(O, "O", out=True)])
     _check(load().dsattn_forward(plan.handle, _ptr(Q), _ptr(K), _ptr(V), _ptr(O),
                                  _stream(stream)), "dsattn_forward")
 
 
 def dsattn_forward_ctx(plan: Plan, Q, Kctx, Vctx, O, stream=None):
+    plan.check("dsattn_forward_ctx", [plan.frames(Q, "Q"), plan.ctx(Kctx, "Kctx"),
+                                      plan.ctx(Vctx, "Vctx"), plan.frames(O, "O", out=True)])
     _check(load().dsattn_forward_ctx(plan.handle, _ptr(Q), _ptr(Kctx), _ptr(Vctx), _ptr(O),
                                      _stream(stream)), "dsattn_forward_ctx")
 
 
 def dsattn_copy_probe(dst, src, nbytes, stream=None):
+    _check_tensors("dsattn_copy_probe",
+                   [(t, name, ("min", -(-int(nbytes) // t.element_size())), None)
+                    for t, name in ((dst, "dst"), (src, "src")) if hasattr(t, "element_size")],
+                   "current")
     _check(load().dsattn_copy_probe(_ptr(dst), _ptr(src), int(nbytes), _stream(stream)),
            "dsattn_copy_probe")
 
@@ -305,10 +373,22 @@ def dsattn_groupnorm_workspace(clip_len, n_clips, spatial, channels, groups, io_
     return int(out.value)
 
 
+def _gn_items(desc, X, Y, gamma, beta, stats):
+    n = desc.clip_len * desc.n_clips * desc.spatial * desc.channels
+    return [(X, "X", n, desc.io_dtype), (Y, "Y", n, desc.io_dtype),
+            (gamma, "gamma", desc.channels, DSATTN_F32), (beta, "beta", desc.channels, DSATTN_F32),
+            (stats, "stats", 2 * desc.groups, DSATTN_F32)]
+
+
 def dsattn_groupnorm(clip_len, n_clips, spatial, channels, groups, X, Y, workspace,
                      workspace_bytes, gamma=None, beta=None, stats=None, io_dtype=DSATTN_BF16,
                      eps=1e-5, stream=None):
     desc = DsattnGnDesc(clip_len, n_clips, spatial, channels, groups, io_dtype, float(eps))
+    items = _gn_items(desc, X, Y, gamma, beta, stats)
+    if hasattr(workspace, "element_size"):
+        items.append((workspace, "workspace",
+                      ("min", -(-int(workspace_bytes) // workspace.element_size())), None))
+    _check_tensors("dsattn_groupnorm", items, "current")
     _check(load().dsattn_groupnorm(ctypes.byref(desc), _ptr(X), _ptr(gamma), _ptr(beta), _ptr(Y),
                                    _ptr(stats), _ptr(workspace), int(workspace_bytes),
                                    _stream(stream)), "dsattn_groupnorm")
@@ -321,6 +401,7 @@ def dsattn_groupnorm_static_max_bytes() -> int:
 def dsattn_groupnorm_static(clip_len, n_clips, spatial, channels, groups, X, Y, gamma=None,
                             beta=None, stats=None, io_dtype=DSATTN_BF16, eps=1e-5, stream=None):
     desc = DsattnGnDesc(clip_len, n_clips, spatial, channels, groups, io_dtype, float(eps))
+    _check_tensors("dsattn_groupnorm_static", _gn_items(desc, X, Y, gamma, beta, stats), "current")
     _check(load().dsattn_groupnorm_static(ctypes.byref(desc), _ptr(X), _ptr(gamma), _ptr(beta),
                                           _ptr(Y), _ptr(stats), _stream(stream)),
            "dsattn_groupnorm_static")
@@ -340,6 +421,12 @@ def dsattn_temporal_conv(clip_len, n_clips, spatial, c_in, c_out, reach, X, W, Y
                          io_dtype=DSATTN_BF16, out_dtype=None, flags=0, stream=None):
     desc = DsattnConvDesc(clip_len, n_clips, spatial, c_in, c_out, reach, io_dtype,
                           io_dtype if out_dtype is None else out_dtype, flags)
+    rows = clip_len * n_clips * spatial
+    _check_tensors("dsattn_temporal_conv",
+                   [(X, "X", rows * c_in, desc.io_dtype),
+                    (W, "W", (2 * reach + 1) * c_out * c_in, desc.io_dtype),
+                    (bias, "bias", c_out, DSATTN_F32), (Y, "Y", rows * c_out, desc.out_dtype)],
+                   "current")
     _check(load().dsattn_temporal_conv(ctypes.byref(desc), _ptr(X), _ptr(W), _ptr(bias), _ptr(Y),
                                        _stream(stream)), "dsattn_temporal_conv")
 
@@ -367,6 +454,13 @@ def dsattn_linear(rows, c_in, c_out, X, Ws, Ys, biases=None, io_dtype=DSATTN_BF1
         raise ValueError("Ws, Ys and biases must have the same length")
     desc = DsattnLinearDesc(rows, c_in, c_out, n, io_dtype,
                             io_dtype if out_dtype is None else out_dtype, flags)
+    items = [(X, "X", rows * c_in, desc.io_dtype)]
+    for g in range(n):
+        items.append((Ws[g], f"W[{g}]", c_out * c_in, desc.io_dtype))
+        items.append((Ys[g], f"Y[{g}]", rows * c_out, desc.out_dtype))
+        if biases is not None:
+            items.append((biases[g], f"bias[{g}]", c_out, DSATTN_F32))
+    _check_tensors("dsattn_linear", items, "current")
     _check(load().dsattn_linear(ctypes.byref(desc), _ptr(X), _ptr_array(Ws, n),
                                 None if biases is None else _ptr_array(biases, n),
                                 _ptr_array(Ys, n), _stream(stream)), "dsattn_linear")

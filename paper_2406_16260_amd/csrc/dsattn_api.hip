@@ -71,6 +71,7 @@ static void run_planner(dsattn_plan_t &pl)
     if (!force_generic && mfma_plan(pl)) return;
     // generic kernel: one wavefront per (clip, position, head)
     li.kernel = 0;
+    li.variant = -1;
     li.heads_per_wave = 1;
     li.clips_per_task = 1;
     li.block_threads = 64;

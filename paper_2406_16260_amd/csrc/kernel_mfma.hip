@@ -19,15 +19,21 @@ const VariantTable kTables[] = {mfma_variants_d160, mfma_variants_d128, mfma_var
                                 mfma_variants_d80,  mfma_variants_d64,  mfma_variants_d40,
                                 mfma_variants_d32};
 
-const MfmaVariant *find_variant(int D, int HPW, int NLT, int NGT, bool out_f32)
+// Position of a variant in the concatenation of the per-head_dim tables: the id that
+// dsattn_launch_info reports.
+const MfmaVariant *find_variant(int D, int HPW, int NLT, int NGT, bool out_f32, int *id = nullptr)
 {
+    int base = 0;
     for (VariantTable tab : kTables) {
         int n = 0;
         const MfmaVariant *v = tab(&n);
         for (int i = 0; i < n; ++i)
             if (v[i].D == D && v[i].HPW == HPW && v[i].NLT == NLT && v[i].NGT == NGT &&
-                v[i].out_f32 == out_f32)
+                v[i].out_f32 == out_f32) {
+                if (id) *id = base + i;
                 return &v[i];
+            }
+        base += n;
     }
     return nullptr;
 }
@@ -43,7 +49,8 @@ int env_int(const char *name, int dflt)
 bool mfma_plan(dsattn_plan_t &pl)
 {
     const dsattn_desc &d = pl.desc;
-    if (d.io_dtype != DSATTN_BF16 || d.clip_len != 16) return false;
+    // The kernel works on query tiles of 16 frames; a clip is a whole number of them.
+    if (d.io_dtype != DSATTN_BF16 || d.clip_len % 16 != 0) return false;
     if (pl.C % 8 != 0) return false;
     // the kernel addresses the 16 frame rows of a tile with 32-bit byte offsets
     if ((int64_t)d.spatial * pl.C * 2 * 16 >= ((int64_t)1 << 32)) return false;
@@ -51,31 +58,45 @@ bool mfma_plan(dsattn_plan_t &pl)
     // global key tiles: variants exist for 0, 1 and 4 tiles; a partly used tile is masked
     if (G > 64) return false;
     const int NGT = G == 0 ? 0 : (G <= 16 ? 1 : 4);
-    const int R = 16 + 2 * d.local_ctx;
+    // Frames a tile's local scope can reach beyond the tile on each side: up to the end of the
+    // clip's local range (the rest of the clip plus the neighbour's context frames), or the
+    // sliding window's radius when that is shorter.  With 16-frame clips and no window this is
+    // the clip's local context width.
+    const int64_t reach = (int64_t)d.clip_len - 16 + d.local_ctx;
+    const int64_t wr64 = pl.window >= 0 ? std::min<int64_t>(pl.window, reach) : reach;
+    if (wr64 > 16) return false;  // local key tiles: variants exist for 1 to 3
+    const int wr = (int)wr64;
+    const int n_tiles = pl.F / 16;
+    const int R = 16 + 2 * wr;
     const int NLT = (R + 15) / 16;
     const bool out_f32 = d.out_dtype == DSATTN_F32;
 
     // heads per wavefront: prefer the variant that keeps two wavefronts per SIMD (more loads in
     // flight, compute of one wavefront hidden behind the other), then the widest rows; a
     // wavefront never straddles two positions
+    // The set-union option is built into the variants with one global key tile, and into the
+    // four-tile variants that run one wavefront per SIMD (head_dim 160 and 128): with that option
+    // and four tiles only those are candidates.
+    const bool need_wpe1 = (d.flags & DSATTN_FLAG_DEDUP_GLOBAL) && NGT == 4;
     const MfmaVariant *var = nullptr;
+    int var_id = -1;
     const int force_hpw = env_int("DSATTN_HEADS_PER_WAVE", 0);
     for (int wpe : {2, 1}) {
+        if (need_wpe1 && wpe != 1) continue;
         for (int cand : {4, 2, 1}) {
             if (force_hpw && cand != force_hpw) continue;
             if (d.heads % cand != 0) continue;
-            const MfmaVariant *v = find_variant(d.head_dim, cand, NLT, NGT, out_f32);
+            int id = -1;
+            const MfmaVariant *v = find_variant(d.head_dim, cand, NLT, NGT, out_f32, &id);
             if (v && v->WPE == wpe) {
                 var = v;
+                var_id = id;
                 break;
             }
         }
         if (var) break;
     }
     if (!var) return false;
-    // the set-union option is built into the variants with one global key tile, and into the
-    // four-tile variants that run one wavefront per SIMD (head_dim 160 and 128)
-    if ((d.flags & DSATTN_FLAG_DEDUP_GLOBAL) && NGT == 4 && var->WPE != 1) return false;
     const int hpw = var->HPW;
     const int lds_wave = (2 * R + 16) * row_stride_bytes(d.head_dim * hpw);
     if (lds_wave > kLdsPerCu) return false;
@@ -110,9 +131,11 @@ bool mfma_plan(dsattn_plan_t &pl)
     const double slots = (double)kCus * blocks_cu;
     int best_nc = 1;
     double best_cost = 1e300;
-    for (int nc = 1; nc <= d.n_clips; ++nc) {
-        const int m = (d.n_clips + nc - 1) / nc;
-        if ((d.n_clips + m - 1) / m != nc) continue;  // same chunking as a smaller nc
+    // (past a few dozen rounds the fill term is 1 and more chunks only add traffic)
+    const int nc_cap = (int)std::min<double>(n_tiles, std::max(4096.0, 64.0 * slots / bpc));
+    for (int nc = 1; nc <= nc_cap; ++nc) {
+        const int m = (n_tiles + nc - 1) / nc;
+        if ((n_tiles + m - 1) / m != nc) continue;  // same chunking as a smaller nc
         const double rounds = (double)bpc * nc / slots;
         const double whole = std::floor(rounds);
         const double rem = rounds - whole;
@@ -122,16 +145,16 @@ bool mfma_plan(dsattn_plan_t &pl)
                                                                               : std::max(rem, 0.6))
                                                 : 0.0);
         const double fill = rounds_eff / rounds;
-        const double kv = (16.0 * m + (nc > 1 ? 2.0 * d.local_ctx : 0.0) + G) / (16.0 * m);
+        const double kv = (16.0 * m + (nc > 1 ? 2.0 * wr : 0.0) + G) / (16.0 * m);
         const double cost = (2.0 + 2.0 * kv) / 4.0 * fill;
         if (cost < best_cost - 1e-12) {
             best_cost = cost;
             best_nc = nc;
         }
     }
-    int m = (d.n_clips + best_nc - 1) / best_nc;
-    m = std::max(1, std::min(d.n_clips, env_int("DSATTN_CLIPS_PER_TASK", m)));
-    const int NC = (d.n_clips + m - 1) / m;
+    int m = (n_tiles + best_nc - 1) / best_nc;
+    m = std::max(1, std::min(n_tiles, env_int("DSATTN_CLIPS_PER_TASK", m)));
+    const int NC = (n_tiles + m - 1) / m;
     if ((int64_t)RG * NC > 0x7fffffffLL) return false;
 
     dsattn_launch_info &li = pl.launch;
@@ -143,6 +166,18 @@ bool mfma_plan(dsattn_plan_t &pl)
     li.n_tasks = RG * NC;
     li.block_threads = 64 * wpb;
     li.lds_bytes = lds_wave * wpb;
+    li.variant = var_id;
+    li.ring_reach = wr;
+
+    // everything a launch needs that does not depend on the tensors
+    pl.mfma_fn = var->fn;
+    pl.gdup = 0;  // entries that repeat an earlier one (the kernel takes at most 64 entries)
+    for (size_t j = 0; j < pl.global_idx.size() && j < 64; ++j)
+        for (size_t jj = 0; jj < j; ++jj)
+            if (pl.global_idx[jj] == pl.global_idx[j]) {
+                pl.gdup |= (uint64_t)1 << j;
+                break;
+            }
     return true;
 }
 
@@ -152,22 +187,17 @@ bool mfma_plan(dsattn_plan_t &pl)
 // the maximum: plans that share a variant must not lower each other's limit.
 hipError_t mfma_prepare(const dsattn_plan_t &pl)
 {
-    const dsattn_desc &d = pl.desc;
-    const dsattn_launch_info &li = pl.launch;
-    const MfmaVariant *v = find_variant(d.head_dim, li.heads_per_wave, li.local_tiles,
-                                        li.global_tiles, d.out_dtype == DSATTN_F32);
-    if (!v) return hipErrorInvalidValue;
-    return hipFuncSetAttribute(v->fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
+    if (!pl.mfma_fn) return hipErrorInvalidValue;
+    return hipFuncSetAttribute(pl.mfma_fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
 }
 
 hipError_t launch_mfma(const dsattn_plan_t &pl, const void *Q, const void *K, const void *V,
                        void *O, bool ctx_mode, hipStream_t st)
 {
+    // the variant and the duplicate mask were resolved by mfma_plan: nothing is searched here
     const dsattn_desc &d = pl.desc;
     const dsattn_launch_info &li = pl.launch;
-    const MfmaVariant *v = find_variant(d.head_dim, li.heads_per_wave, li.local_tiles,
-                                        li.global_tiles, d.out_dtype == DSATTN_F32);
-    if (!v) return hipErrorInvalidValue;
+    if (!pl.mfma_fn) return hipErrorInvalidValue;
     const int wpb = li.block_threads / 64;
 
     MfmaArgs a;
@@ -176,14 +206,17 @@ hipError_t launch_mfma(const dsattn_plan_t &pl, const void *Q, const void *K, co
     a.V = (const __bf16 *)V;
     a.O = O;
     a.gidx = pl.d_global_idx;
-    a.N = d.n_clips;
+    const int n_tiles = pl.F / 16;
+    a.N = n_tiles;
     a.F = pl.F;
     a.h = d.heads;
-    a.w = d.local_ctx;
+    a.w = li.ring_reach;
     a.G = (int32_t)pl.global_idx.size();
-    a.R = 16 + 2 * d.local_ctx;
+    a.R = 16 + 2 * li.ring_reach;
+    a.clip_len = d.clip_len;
+    a.wl = d.local_ctx;
     a.window = pl.window;
-    a.M = ctx_mode ? 1 : li.clips_per_task;
+    a.M = ctx_mode ? d.clip_len / 16 : li.clips_per_task;
     a.cstride = ctx_mode ? (int64_t)pl.lk_max * d.spatial * pl.C : 0;
     a.RG = d.spatial * (d.heads / li.heads_per_wave);
     a.BPC = a.RG / wpb;
@@ -192,22 +225,16 @@ hipError_t launch_mfma(const dsattn_plan_t &pl, const void *Q, const void *K, co
     a.sc = pl.scale * 1.4426950408889634f;
     a.gshift = (d.bias_global - d.bias_local) / pl.scale;
     a.dedup = (d.flags & DSATTN_FLAG_DEDUP_GLOBAL) ? 1 : 0;
-    a.gdup = 0;  // entries that repeat an earlier one (the kernel is used for at most 64 entries)
-    for (size_t j = 0; j < pl.global_idx.size() && j < 64; ++j)
-        for (size_t jj = 0; jj < j; ++jj)
-            if (pl.global_idx[jj] == pl.global_idx[j]) {
-                a.gdup |= (uint64_t)1 << j;
-                break;
-            }
+    a.gdup = pl.gdup;
 
     // the grid must be exactly chunks x workgroups-per-chunk, each workgroup wpb whole row groups
-    const int NC = (d.n_clips + a.M - 1) / a.M;
+    const int NC = (n_tiles + a.M - 1) / a.M;
     if (a.RG % wpb != 0 || (!ctx_mode && (int64_t)a.BPC * NC * wpb != (int64_t)li.n_tasks) ||
         (int64_t)a.BPC * NC > 0x7fffffffLL)
         return hipErrorInvalidValue;
 
     void *params[] = {&a};
-    return hipLaunchKernel(v->fn, dim3((unsigned)(a.BPC * NC)), dim3((unsigned)li.block_threads),
+    return hipLaunchKernel(pl.mfma_fn, dim3((unsigned)(a.BPC * NC)), dim3((unsigned)li.block_threads),
                            params, (size_t)li.lds_bytes, st);
 }
 

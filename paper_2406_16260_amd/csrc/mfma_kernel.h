@@ -1,5 +1,12 @@
 // bf16 MFMA streaming kernel for Dual-scope temporal attention on gfx950 (Section 4.2 of the
-// paper: keys/values of a clip = Concat(local frames, global frames); clip length 16).
+// paper: keys/values of a clip = Concat(local frames, global frames)).
+//
+// The unit of work is a "query tile": 16 consecutive frames of one clip (the whole clip when a
+// clip has 16 frames; below, "clip" in the description of the walk means such a tile).  A tile
+// sees the frames within w of it that lie in its clip's local range (the clip's own frames plus
+// the context frames of its two neighbours, Section 4.1), where w is the distance the local scope
+// can reach beyond the tile: the clip's local context width for 16-frame clips, and for longer
+// clips the sliding-window radius of Section 4.2 (or, without a window, the rest of the clip).
 //
 // Work decomposition.  One wavefront owns a "row group": one spatial position and HPW
 // consecutive heads, whose channels are SEG = HPW*D contiguous bf16 per frame, and walks M
@@ -44,9 +51,14 @@ struct MfmaArgs {
     const __bf16 *Q, *K, *V;
     void *O;
     const int32_t *gidx;  // device [G]
-    int32_t N, F, h, w, G, R;
+    int32_t N;    // query tiles of 16 frames in the video = F / 16 (= clips when a clip has 16 frames)
+    int32_t F, h;
+    int32_t w;    // frames the ring holds beyond a query tile on each side, R = 16 + 2 w
+    int32_t G, R;
+    int32_t clip_len;  // F_clip, a multiple of 16
+    int32_t wl;        // local context width of a clip (frames taken from each neighbouring clip)
     int32_t window;  // sliding-window radius of the local scope, -1 = none
-    int32_t M;    // clips per chunk
+    int32_t M;    // query tiles per chunk
     int32_t RG;   // row groups = P * h / HPW
     int32_t BPC;  // workgroups per chunk = RG / WPB
     int32_t C;
@@ -57,8 +69,9 @@ struct MfmaArgs {
     int32_t dedup;   // set union: drop a global entry whose frame the query already sees
     uint64_t gdup;   // bit j: global entry j repeats an earlier global entry
     int64_t cstride; // 0: K and V are [F, P, C].  Otherwise they are materialised contexts
-                     // [N, lk_max, P, C] (clip i: its local frames ascending, then the global
-                     // entries) with cstride = lk_max * P * C elements per clip, and M = 1
+                     // [n_clips, lk_max, P, C] (clip i: its local frames ascending, then the
+                     // global entries) with cstride = lk_max * P * C elements per clip, and a
+                     // chunk is exactly one clip (M = clip_len / 16)
 };
 
 struct MfmaVariant {
@@ -148,13 +161,18 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
     // Materialised context (one clip per chunk): row j of clip c0's slab is local frame lo + j,
     // then global entry j - (hi - lo).  Moving the bases so that "frame f" of the slab sits at
     // f * FSB keeps every local address below as it is; global entry j becomes "frame" hi + j.
+    // Frames that may be read at all: the video, or the clip's slab.
     int gfirst = -1;
+    int flo = 0, fhi = F;
     if (a.cstride != 0) {
-        const int lo = max(0, 16 * c0 - w), hi = min(F, 16 * c0 + 16 + w);
-        const int64_t shift = ((int64_t)c0 * a.cstride - (int64_t)lo * a.FS) * 2;
+        const int ci = ck;  // one clip per chunk
+        const int lo = max(0, ci * a.clip_len - a.wl), hi = min(F, (ci + 1) * a.clip_len + a.wl);
+        const int64_t shift = ((int64_t)ci * a.cstride - (int64_t)lo * a.FS) * 2;
         Kb += shift;
         Vb += shift;
         gfirst = hi;
+        flo = lo;
+        fhi = hi;
     }
 
     // per-lane load geometry: lane-load `r` covers tile row fq[r], 16-byte chunk cq;
@@ -178,11 +196,11 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
     };
 
     // 16 consecutive frames starting at frame0 (wave-uniform); rows >= nrows and frames
-    // outside [0, F) give zeros
-    auto load_rows = [&](const unsigned char *base, int frame0, int nrows, uint4(&st)[NLD])
-                         __attribute__((always_inline)) {
+    // outside [lo, hi) give zeros
+    auto load_rows = [&](const unsigned char *base, int frame0, int nrows, int lo, int hi,
+                         uint4(&st)[NLD]) __attribute__((always_inline)) {
         const unsigned char *tb = base + (int64_t)frame0 * FSB;
-        if (nrows == 16 && frame0 >= 0 && frame0 + 16 <= F) {
+        if (nrows == 16 && frame0 >= lo && frame0 + 16 <= hi) {
             // whole tile inside the video: no per-lane frame checks
 #pragma unroll
             for (int r = 0; r < NLD; ++r) {
@@ -198,7 +216,7 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
 #pragma unroll
             for (int r = 0; r < NLD; ++r) {
                 const int f = frame0 + fq[r];
-                const bool ok = in_tile(r) && fq[r] < nrows && f >= 0 && f < F;
+                const bool ok = in_tile(r) && fq[r] < nrows && f >= lo && f < hi;
                 uint4 x = make_uint4(0, 0, 0, 0);
                 if (ok) x = *(const uint4 *)(tb + voff[r]);
                 st[r] = x;
@@ -314,10 +332,10 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
 
     // boundary frames that precede the first bulk tile: 2w rows, 16 per local tile
     if constexpr (NLT >= 2) {
-        load_rows(Kb, 16 * c0 - w, min(16, 2 * w), stK);
-        load_rows(Vb, 16 * c0 - w, min(16, 2 * w), stV);
+        load_rows(Kb, 16 * c0 - w, min(16, 2 * w), flo, fhi, stK);
+        load_rows(Vb, 16 * c0 - w, min(16, 2 * w), flo, fhi, stV);
     }
-    load_rows(Qb, 16 * c0, 16, stQ);
+    load_rows(Qb, 16 * c0, 16, 0, F, stQ);
     if constexpr (NGT > 0) load_global_tile(0);
     if constexpr (NLT >= 2) {
         const int s0 = (16 * c0) % R;  // slot of frame f is (f + w) mod R
@@ -329,16 +347,16 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
         const int nrows = min(16, 2 * w - 16 * tl);
         if (nrows > 0) {
             const int f0 = 16 * c0 - w + 16 * tl;
-            load_rows(Kb, f0, nrows, stK);
-            load_rows(Vb, f0, nrows, stV);
+            load_rows(Kb, f0, nrows, flo, fhi, stK);
+            load_rows(Vb, f0, nrows, flo, fhi, stV);
             const int s0 = (16 * c0 + 16 * tl) % R;
             store_rows(kring, s0, nrows, R, stK);
             store_rows(vring, s0, nrows, R, stV);
         }
     }
     // first bulk tile of K/V: frames [16 c0 + w, +16)
-    load_rows(Kb, 16 * c0 + w, 16, stK);
-    load_rows(Vb, 16 * c0 + w, 16, stV);
+    load_rows(Kb, 16 * c0 + w, 16, flo, fhi, stK);
+    load_rows(Vb, 16 * c0 + w, 16, flo, fhi, stV);
 
     // global context into registers in MFMA operand form, staged through the Q/O buffer
 #pragma unroll
@@ -404,17 +422,22 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
         store_tile(kring, s_bulk, R, stK);
         store_tile(vring, s_bulk, R, stV);
         if (i + 1 < c1) {
-            load_rows(Qb, 16 * (i + 1), 16, stQ);
-            load_rows(Kb, 16 * (i + 1) + w, 16, stK);
-            load_rows(Vb, 16 * (i + 1) + w, 16, stV);
+            load_rows(Qb, 16 * (i + 1), 16, 0, F, stQ);
+            load_rows(Kb, 16 * (i + 1) + w, 16, flo, fhi, stK);
+            load_rows(Vb, 16 * (i + 1) + w, 16, flo, fhi, stV);
         }
         wave_sync();
 
         // validity of this lane's local keys: C/D row 4*lg + e of local tile tl is ring slot
         // 16 tl + 4 lg + e, holding frame 16 i - w + ((slot - b0) mod R)
+        // The tile's clip and that clip's local range [clo, chi): the clip's own frames plus wl
+        // frames of each neighbouring clip, cut at the ends of the video (Section 4.1).
+        const int clip = (16 * i) / a.clip_len;
+        const int clo = max(0, clip * a.clip_len - a.wl);
+        const int chi = min(F, (clip + 1) * a.clip_len + a.wl);
         bool lvalid[NLT][4];
         int arow[NLT];  // ring row this lane feeds as MFMA row l16 of local tile tl (clamped)
-        const bool interior = 16 * i - w >= 0 && 16 * i + 16 + w <= F;
+        const bool interior = 16 * i - w >= clo && 16 * i + 16 + w <= chi;
 #pragma unroll
         for (int tl = 0; tl < NLT; ++tl) {
             arow[tl] = min(16 * tl + l16, R - 1);
@@ -426,7 +449,7 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
                     int rel = s - b0;
                     if (rel < 0) rel += R;
                     const int f = 16 * i - w + rel;
-                    ok = ok && f >= 0 && f < F;
+                    ok = ok && f >= clo && f < chi;
                     // sliding window: key frame f against this lane's query frame 16 i + l16
                     if (a.window >= 0) ok = ok && abs(rel - w - l16) <= a.window;
                 }
@@ -439,7 +462,7 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
         // visible local key of that query
         uint32_t ghid = 0;
         if (kDedup && a.dedup) {
-            const int lo = max(0, 16 * i - w), hi = min(F, 16 * i + 16 + w);
+            const int lo = max(clo, 16 * i - w), hi = min(chi, 16 * i + 16 + w);
             const int aq = 16 * i + l16;
 #pragma unroll
             for (int tg = 0; tg < NGT; ++tg)

@@ -26,6 +26,10 @@ struct dsattn_plan_s {
     int32_t *d_global_idx = nullptr;  // device [max(1, n_global)]
 
     dsattn_launch_info launch;
+
+    // resolved once by the planner for the matrix-core kernel, so that a launch searches nothing
+    const void *mfma_fn = nullptr;  // the variant's kernel
+    uint64_t gdup = 0;              // bit j: global entry j (< 64) repeats an earlier entry
 };
 
 namespace dsattn {

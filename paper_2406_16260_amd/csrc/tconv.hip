@@ -28,7 +28,7 @@
 
 #include <algorithm>
 #include <cstdlib>
-#include <mutex>
+#include <atomic>
 
 #include "dsattn.h"
 #include "plan.h"
@@ -532,22 +532,20 @@ hipError_t conv_launch(const dsattn_conv_desc &d, int64_t M, const ConvVariant *
     if (v) {
         const void *fn = v->fn[d.out_dtype == DSATTN_F32 ? 1 : 0];
         const int lds = conv_lds_bytes(*v);
-        // the default cap on dynamic LDS is 64 KB: raised once per kernel and device
-        static std::mutex mu;
-        static uint64_t prepared[sizeof(kConvVariants) / sizeof(kConvVariants[0])][2] = {};
+        // The default cap on dynamic LDS is 64 KB: raised once per kernel and device.  The launch
+        // path only reads a flag (no lock); two threads that both find it clear both set the
+        // attribute, which is harmless.
+        static std::atomic<uint64_t> prepared[sizeof(kConvVariants) / sizeof(kConvVariants[0])][2];
         int dev = 0;
-        e = hipGetDevice(&dev);
-        if (e == hipSuccess && dev < 64) {
-            std::lock_guard<std::mutex> lock(mu);
-            uint64_t &mask = prepared[v - kConvVariants][d.out_dtype == DSATTN_F32 ? 1 : 0];
-            if (!(mask >> dev & 1)) {
-                e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-                if (e == hipSuccess) mask |= (uint64_t)1 << dev;
-            }
-        } else if (e == hipSuccess) {
-            e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        }
+        e = hipGetDevice(&dev);  // a thread-local read in the runtime
         if (e != hipSuccess) return e;
+        std::atomic<uint64_t> *mask =
+            dev < 64 ? &prepared[v - kConvVariants][d.out_dtype == DSATTN_F32 ? 1 : 0] : nullptr;
+        if (!mask || !(mask->load(std::memory_order_acquire) >> dev & 1)) {
+            e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            if (e != hipSuccess) return e;
+            if (mask) mask->fetch_or((uint64_t)1 << dev, std::memory_order_release);
+        }
         ConvArgs a;
         a.X = X;
         for (int g = 0; g < kMaxGroups; ++g) {

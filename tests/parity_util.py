@@ -82,3 +82,28 @@ def assert_parity(o_dev, ref, out_dtype, positions=None, what=""):
         assert not bad.any(), (f"{what}: {int(bad.sum())} elements beyond the bf16 bar; "
                                f"max-abs {mx:.3e}, worst |ref| {np.abs(ref[bad]).max():.3f}")
     return mx
+
+
+class planner_env:
+    """Pins planner choices (clips per chunk, wavefronts per workgroup) for one case."""
+
+    def __init__(self, clips_per_task=None, waves_per_block=None):
+        self.vals = {"DSATTN_CLIPS_PER_TASK": clips_per_task,
+                     "DSATTN_WAVES_PER_BLOCK": waves_per_block}
+
+    def __enter__(self):
+        import os
+        self.old = {k: os.environ.get(k) for k in self.vals}
+        for k, v in self.vals.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = str(v)
+
+    def __exit__(self, *exc):
+        import os
+        for k, v in self.old.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v

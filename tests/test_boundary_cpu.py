@@ -266,3 +266,156 @@ def test_header_is_plain_c_and_usable_from_c(tmp_path):
                     "-L", libdir, "-l:libdsattn.so", f"-Wl,-rpath,{libdir}"], check=True)
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
     assert out.startswith("ok lk_max=7")
+
+
+# ---------------------------------------------------------------- binding: tensor checks
+# The C ABI takes bare pointers, so the Python wrappers refuse tensors whose size, element type or
+# device does not fit the plan or descriptor before anything reaches a kernel.  Driven here with
+# host-only plans (device = -1) and CPU tensors: no GPU is needed to reach the checks.
+
+def _host_plan(**kw):
+    args = dict(clip_len=4, n_clips=3, local_ctx=1, spatial=5, heads=2, head_dim=8,
+                global_idx=[0, 7], io_dtype=B.DSATTN_BF16, device=-1)
+    args.update(kw)
+    return B.dsattn_plan(**args)
+
+
+def test_binding_refuses_wrong_sized_or_typed_tensors_for_a_plan():
+    import torch
+    plan = _host_plan()
+    n = 12 * 5 * 16
+    good = lambda: torch.zeros(12, 5, 16, dtype=torch.bfloat16)
+    with pytest.raises(ValueError, match="elements"):
+        B.dsattn_forward(plan, torch.zeros(n - 16, dtype=torch.bfloat16), good(), good(), good())
+    with pytest.raises(ValueError, match="elements"):
+        B.dsattn_forward(plan, good(), good(), good(), torch.zeros(n + 1, dtype=torch.bfloat16))
+    with pytest.raises(ValueError, match="dtype"):
+        B.dsattn_forward(plan, good(), torch.zeros(12, 5, 16, dtype=torch.float32), good(), good())
+    with pytest.raises(ValueError, match="dtype"):   # O follows out_dtype (bf16 here)
+        B.dsattn_forward(plan, good(), good(), good(), torch.zeros(12, 5, 16, dtype=torch.float32))
+    with pytest.raises(ValueError, match="contiguous"):
+        B.dsattn_forward(plan, torch.zeros(12, 16, 5, dtype=torch.bfloat16).transpose(1, 2), good(),
+                         good(), good())
+    # well-formed tensors pass the wrapper; the library then refuses the host-only plan
+    with pytest.raises(B.DsattnError) as ei:
+        B.dsattn_forward(plan, good(), good(), good(), good(), stream=0)
+    assert ei.value.code == B.DSATTN_ENODEVICE
+    # materialised contexts are [N, lk_max, P, C]
+    lk = B.dsattn_plan_ctx_max(plan)
+    assert lk == 4 + 2 + 2
+    ctx = lambda k=lk: torch.zeros(3, k, 5, 16, dtype=torch.bfloat16)
+    with pytest.raises(ValueError, match="Kctx"):
+        B.dsattn_gather_context(plan, good(), good(), ctx(lk - 1), ctx(), stream=0)
+    with pytest.raises(ValueError, match="Vctx"):
+        B.dsattn_forward_ctx(plan, good(), ctx(), ctx(lk + 1), good(), stream=0)
+    with pytest.raises(B.DsattnError):
+        B.dsattn_forward_ctx(plan, good(), ctx(), ctx(), good(), stream=0)
+    plan.close()
+    # fp32 output of a bf16 plan
+    plan = _host_plan(out_dtype=B.DSATTN_F32)
+    with pytest.raises(ValueError, match="dtype"):
+        B.dsattn_forward(plan, good(), good(), good(), good(), stream=0)
+    plan.close()
+
+
+def test_binding_refuses_tensors_on_the_wrong_device():
+    import torch
+    plan = B.Plan(None, B.DsattnDesc(4, 3, 1, 5, 2, 8, B.DSATTN_BF16, B.DSATTN_BF16, 0.0, 0, 0.0,
+                                     0.0, 0), 0, device=0)   # a device plan's bookkeeping only
+    t = torch.zeros(12, 5, 16, dtype=torch.bfloat16)
+    with pytest.raises(ValueError, match="device memory expected"):
+        plan.check("dsattn_forward", [plan.frames(t, "Q")])
+    with pytest.raises(ValueError, match="device memory expected"):
+        B.dsattn_copy_probe(t, t.clone(), t.numel() * 2, stream=0)
+    with pytest.raises(ValueError, match="at least"):
+        B.dsattn_copy_probe(t, t.clone(), t.numel() * 2 + 16, stream=0)
+
+
+def test_binding_checks_groupnorm_conv_and_linear_tensors():
+    import torch
+    bf = lambda *s: torch.zeros(*s, dtype=torch.bfloat16)
+    f32 = lambda *s: torch.zeros(*s, dtype=torch.float32)
+    # group normalisation: X, Y [F, P, C]; gamma, beta [C] fp32; stats [2 groups] fp32
+    gn = dict(clip_len=4, n_clips=3, spatial=5, channels=64, groups=4)
+    with pytest.raises(ValueError, match="X"):
+        B.dsattn_groupnorm(**gn, X=bf(12, 5, 32), Y=bf(12, 5, 64), workspace=f32(1024),
+                           workspace_bytes=4096, stream=0)
+    with pytest.raises(ValueError, match="gamma"):
+        B.dsattn_groupnorm(**gn, X=bf(12, 5, 64), Y=bf(12, 5, 64), workspace=f32(1024),
+                           workspace_bytes=4096, gamma=bf(64), stream=0)
+    with pytest.raises(ValueError, match="stats"):
+        B.dsattn_groupnorm_static(**gn, X=bf(12, 5, 64), Y=bf(12, 5, 64), stats=f32(4), stream=0)
+    with pytest.raises(ValueError, match="device memory expected"):
+        B.dsattn_groupnorm_static(**gn, X=bf(12, 5, 64), Y=bf(12, 5, 64), stream=0)
+    # temporal convolution: W [2n + 1, c_out, c_in], Y [F, P, c_out]
+    cv = dict(clip_len=4, n_clips=3, spatial=5, c_in=16, c_out=24, reach=1)
+    with pytest.raises(ValueError, match="W"):
+        B.dsattn_temporal_conv(**cv, X=bf(12, 5, 16), W=bf(1, 24, 16), Y=bf(12, 5, 24), stream=0)
+    with pytest.raises(ValueError, match="Y"):
+        B.dsattn_temporal_conv(**cv, X=bf(12, 5, 16), W=bf(3, 24, 16), Y=bf(12, 5, 16), stream=0)
+    with pytest.raises(ValueError, match="bias"):
+        B.dsattn_temporal_conv(**cv, X=bf(12, 5, 16), W=bf(3, 24, 16), Y=bf(12, 5, 24),
+                               bias=bf(24), stream=0)
+    # projections: every W [c_out, c_in], every Y [rows, c_out]
+    with pytest.raises(ValueError, match=r"W\[1\]"):
+        B.dsattn_linear(60, 16, 24, bf(60, 16), [bf(24, 16), bf(16, 16)], [bf(60, 24), bf(60, 24)],
+                        stream=0)
+    with pytest.raises(ValueError, match=r"Y\[0\]"):
+        B.dsattn_linear(60, 16, 24, bf(60, 16), [bf(24, 16)], [bf(59, 24)], stream=0)
+    with pytest.raises(ValueError, match="dtype"):
+        B.dsattn_linear(60, 16, 24, bf(60, 16), [bf(24, 16)], [f32(60, 24)], stream=0)
+
+
+# ---------------------------------------------------------------- planner: long clips, resolved variant
+
+@pytest.mark.parametrize("D,h", [(160, 8), (80, 8), (40, 8)])
+@pytest.mark.parametrize("clip_len,n_clips", [(32, 72), (48, 48), (288, 8)])
+def test_long_clips_with_a_window_run_the_matrix_core_kernel(D, h, clip_len, n_clips):
+    for w, r, G, reach in ((8, 8, 16, 8), (8, 3, 0, 3), (2, 8, 64, 8), (4, 0, 16, 0), (8, 16, 16, 16)):
+        plan = B.dsattn_plan(clip_len, n_clips, w, 160, h, D, list(range(0, 4 * G, 4)), device=-1,
+                             window=r)
+        i = B.dsattn_plan_launch_info(plan)
+        plan.close()
+        assert i["kernel"] == 1 and i["ring_reach"] == reach, (w, r, G, i)
+        assert i["local_tiles"] == (16 + 2 * reach + 15) // 16
+        # chunks are counted in 16-frame query tiles and cover the video exactly
+        tiles = clip_len * n_clips // 16
+        row_groups = 160 * h // i["heads_per_wave"]
+        assert i["n_tasks"] == row_groups * -(-tiles // i["clips_per_task"])
+    # the window radius (or, with none, the rest of the clip) must fit the on-chip ring
+    for kw in (dict(window=17), dict(window=None), dict(window=9, n_global=17)):
+        g = list(range(kw.get("n_global", 4)))
+        plan = B.dsattn_plan(clip_len, n_clips, 8, 160, h, D, g, device=-1, window=kw["window"])
+        assert B.dsattn_plan_launch_info(plan)["kernel"] == 0, kw
+        plan.close()
+
+
+def test_launch_info_carries_the_resolved_variant():
+    # the kernel variant is looked up once, by dsattn_plan; dsattn_forward launches what the plan
+    # holds.  Distinct shapes resolve to distinct variants, equal shapes to the same one.
+    seen = {}
+    for D, h, w, G, od in ((160, 8, 2, 16, B.DSATTN_BF16), (160, 8, 2, 16, B.DSATTN_F32),
+                           (160, 8, 4, 64, B.DSATTN_BF16), (80, 8, 2, 16, B.DSATTN_BF16),
+                           (40, 8, 2, 16, B.DSATTN_BF16), (40, 8, 4, 64, B.DSATTN_BF16)):
+        ids = []
+        for n_clips in (8, 144):
+            plan = B.dsattn_plan(16, n_clips, w, 12, h, D, list(range(G)), out_dtype=od, device=-1)
+            i = B.dsattn_plan_launch_info(plan)
+            plan.close()
+            assert i["kernel"] == 1 and i["variant"] >= 0
+            ids.append(i["variant"])
+        assert ids[0] == ids[1]
+        assert ids[0] not in seen.values()
+        seen[(D, h, w, G, od)] = ids[0]
+    plan = B.dsattn_plan(16, 8, 2, 12, 8, 48, [0], device=-1)     # no variant for head_dim 48
+    assert B.dsattn_plan_launch_info(plan)["variant"] == -1
+    plan.close()
+
+
+def test_planning_a_very_long_video_is_quick():
+    import time
+    t0 = time.perf_counter()
+    plan = B.dsattn_plan(16, 1 << 20, 2, 1, 8, 160, [0, 5, 9], device=-1)   # 16.8 M frames
+    i = B.dsattn_plan_launch_info(plan)
+    plan.close()
+    assert i["kernel"] == 1 and time.perf_counter() - t0 < 2.0

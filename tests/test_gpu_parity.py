@@ -197,29 +197,7 @@ def test_copy_probe_copies():
 
 # ---------------------------------------------------------------- bf16 MFMA streaming kernel
 
-class planner_env:
-    """Pins planner choices (clips per chunk, wavefronts per workgroup) for one case."""
-
-    def __init__(self, clips_per_task=None, waves_per_block=None):
-        self.vals = {"DSATTN_CLIPS_PER_TASK": clips_per_task,
-                     "DSATTN_WAVES_PER_BLOCK": waves_per_block}
-
-    def __enter__(self):
-        import os
-        self.old = {k: os.environ.get(k) for k in self.vals}
-        for k, v in self.vals.items():
-            if v is None:
-                os.environ.pop(k, None)
-            else:
-                os.environ[k] = str(v)
-
-    def __exit__(self, *exc):
-        import os
-        for k, v in self.old.items():
-            if v is None:
-                os.environ.pop(k, None)
-            else:
-                os.environ[k] = v
+planner_env = U.planner_env
 
 
 def run_mfma_case(n_clips, w, P, h, D, g, gen="correlated", scale=0.0, clips_per_task=None,
@@ -556,9 +534,13 @@ def test_randomised_shapes_against_oracle():
         ref = U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g, window=window, bias_global=bg)
         o, info = U.library_forward(q, k, v, clip_len, n_clips, w, h, g, out_dtype="f32",
                                     window=window, bias_global=bg)
-        # MFMA variants: clip length 16, head_dim 32/40/64/80/96/128/160 with any head count,
-        # w <= 16 with up to 16 global frames, w <= 8 with 17..64
-        expect_mfma = clip_len == 16 and D != 24 and (w <= 16 if G <= 16 else w <= 8)
+        # MFMA variants: clips of whole 16-frame tiles, head_dim 32/40/64/80/96/128/160 with any
+        # head count; the frames a tile's local scope reaches beyond the tile (the window radius,
+        # at most the rest of the clip's local range) <= 16 with up to 16 global frames, <= 8
+        # with 17..64
+        reach = clip_len - 16 + w
+        reach = reach if window is None else min(window, reach)
+        expect_mfma = clip_len % 16 == 0 and D != 24 and (reach <= 16 if G <= 16 else reach <= 8)
         assert info["kernel"] == (1 if expect_mfma else 0), (info, case)
         U.assert_parity(o, ref, "f32", what=f"random case {case}")
 
