@@ -25,21 +25,125 @@ METRIC = "dual-scope attn query-frame-positions/s at 1 GPU; % of HBM roofline"
 
 
 def measured_traffic(workload, info):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE and WRITE_SIZE runs, scaled by the copy kernel), or None when no summary matches
-    this launch shape.  Counters cannot be read from inside the timed process."""
+    """HBM bytes per launch of the dominant kernel, read from the committed rocprofv3 --pmc
+    summary (FETCH_SIZE and WRITE_SIZE runs, scaled by the copy kernel), and a string saying
+    where the figure comes from; (None, reason) when no summary matches this launch shape.
+    Counters cannot be read from inside the timed process: the figure is that of an earlier,
+    separate profiler run of the same launch, not of this run."""
     import re
-    path = os.path.join(ROOT, "profiles", f"dsattn_mfma_kernel_{workload}.md")
+    rel = os.path.join("profiles", f"dsattn_mfma_kernel_{workload}.md")
+    path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
-        return None
+        return None, f"no counter summary {rel}"
     text = open(path).read()
     key = (f"{workload}:kernel={info['kernel']}:hpw={info['heads_per_wave']}:"
            f"clips_per_task={info['clips_per_task']}:block_threads={info['block_threads']}")
     mk = re.search(r"^launch_key = (\S+)$", text, re.M)
     mt = re.search(r"^traffic_bytes_per_launch = (\d+)$", text, re.M)
-    if not mk or not mt or mk.group(1) != key:
-        return None
-    return int(mt.group(1))
+    if not mk or not mt:
+        return None, f"{rel} holds no traffic figure"
+    if mk.group(1) != key:
+        return None, f"{rel} was taken with another launch shape ({mk.group(1)}), this run: {key}"
+    return int(mt.group(1)), (f"{rel}: FETCH_SIZE + WRITE_SIZE of a separate rocprofv3 --pmc run of "
+                              "this launch shape made when the summary was committed; not "
+                              "measured in this process")
+
+
+def time_launches(B, torch, stream, plans_and_sets, n_sets, warmup, steps):
+    """Event-timed launches of one or several plans run back to back (one step = every plan
+    once).  plans_and_sets: [(plan, [(q, k, v, o), ...])].  Returns per-plan lists of ms."""
+    for r in range(warmup):
+        for plan, sets in plans_and_sets:
+            B.dsattn_forward(plan, *sets[r % n_sets], stream)
+    n = len(plans_and_sets)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(n + 1)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    for s in range(steps):
+        ev[s][0].record(stream)
+        for j, (plan, sets) in enumerate(plans_and_sets):
+            B.dsattn_forward(plan, *sets[s % n_sets], stream)
+            ev[s][j + 1].record(stream)
+    torch.cuda.synchronize()
+    return [[ev[s][j].elapsed_time(ev[s][j + 1]) for s in range(steps)] for j in range(n)]
+
+
+def other_workloads(B, torch, synth, np, stream, dev, c3_level, steps=20, warmup=5):
+    """The workloads the headline does not time, each with its own buffers, 20 event-timed
+    launches after 5 untimed ones: C1 (three buffer sets in rotation: its tensors would
+    otherwise sit in the Infinity Cache), C2, the four levels of C4 back to back, and two
+    variations on the headline tensors (the paper's own scope sizes; the paper's 288-frame
+    clips with the local scope as a sliding window)."""
+    out = {}
+
+    def summarise(times, info, extra=None):
+        ms = float(np.mean(times))
+        d = {"ms": round(ms, 4), "ms_min": round(float(np.min(times)), 4),
+             "ms_median": round(float(np.median(times)), 4),
+             "algorithmic_bytes": info["algorithmic_bytes"],
+             "GBps": round(info["algorithmic_bytes"] / ms / 1e6, 1),
+             "frac": round(info["algorithmic_bytes"] / ms / 1e6 / HBM_PEAK_GBPS, 4),
+             "launch": info}
+        if extra:
+            d.update(extra)
+        return d
+
+    for name in ("C1", "C2", "C4"):
+        wl = synth.WORKLOADS[name]
+        gidx = synth.global_idx_for(wl)
+        total_bytes = sum(4 * wl.F * lv.P * lv.C * 2 for lv in wl.levels)
+        n_sets = 3 if total_bytes < (1 << 30) else 1
+        pas = []
+        for lv in wl.levels:
+            sets = []
+            for r in range(n_sets):
+                q, k, v = synth.make_qkv(wl, lv, device=dev, seed_offset=100 * r)
+                sets.append((q, k, v, torch.empty_like(q)))
+            plan = B.dsattn_plan(wl.clip_len, wl.n_clips, wl.local_ctx, lv.P, lv.heads,
+                                 lv.head_dim, gidx, io_dtype=B.DSATTN_BF16,
+                                 out_dtype=B.DSATTN_BF16, device=0)
+            pas.append((plan, sets))
+        times = time_launches(B, torch, stream, pas, n_sets, warmup, steps)
+        infos = [B.dsattn_plan_launch_info(plan) for plan, _ in pas]
+        if len(pas) == 1:
+            tr, src = measured_traffic(name, infos[0])
+            out[name] = summarise(times[0], infos[0], {"buffer_sets": n_sets, "traffic": tr,
+                                                       "traffic_source": src})
+        else:
+            per = {lv.name: summarise(t, i) for lv, t, i in zip(wl.levels, times, infos)}
+            tot_ms = sum(v["ms"] for v in per.values())
+            tot_b = sum(i["algorithmic_bytes"] for i in infos)
+            out[name] = {"ms": round(tot_ms, 4), "algorithmic_bytes": tot_b,
+                         "GBps": round(tot_b / tot_ms / 1e6, 1),
+                         "frac": round(tot_b / tot_ms / 1e6 / HBM_PEAK_GBPS, 4),
+                         "per_level_ms": [per[lv.name]["ms"] for lv in wl.levels],
+                         "per_level_frac": [per[lv.name]["frac"] for lv in wl.levels],
+                         "levels": per, "buffer_sets": n_sets}
+        for plan, sets in pas:
+            plan.close()
+        del pas, sets
+        torch.cuda.empty_cache()
+
+    # variations on the headline level's tensors (2,304 frames, 10 x 16 positions, 8 x 160)
+    wl = synth.WORKLOADS["C3"]
+    lv = c3_level["level"]
+    g16 = synth.stride_global_idx(wl.F, 16)
+    variations = {
+        # Section 4.2 / 5.1: 8 frames from each neighbouring clip, 16 global frames, L_k = 48
+        "C3_w8_G16": dict(clip_len=16, n_clips=144, local_ctx=8, window=None),
+        # Section 4: the clip of one of eight devices (288 frames), the local scope as a window of
+        # 8 frames to each side of the query frame, 8 context frames from each neighbouring clip
+        "C3_8x288_w8_r8_G16": dict(clip_len=288, n_clips=8, local_ctx=8, window=8),
+    }
+    for name, kw in variations.items():
+        plan = B.dsattn_plan(kw["clip_len"], kw["n_clips"], kw["local_ctx"], lv.P, lv.heads,
+                             lv.head_dim, g16, io_dtype=B.DSATTN_BF16, out_dtype=B.DSATTN_BF16,
+                             device=0, window=kw["window"])
+        sets = [(c3_level["q"], c3_level["k"], c3_level["v"], c3_level["o"])]
+        times = time_launches(B, torch, stream, [(plan, sets)], 1, warmup, steps)
+        out[name] = summarise(times[0], B.dsattn_plan_launch_info(plan),
+                              {"config": {k: v for k, v in kw.items()}})
+        plan.close()
+    return out
 
 
 def main():
@@ -50,6 +154,8 @@ def main():
     ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4"])
     ap.add_argument("--no-cpu-baseline", action="store_true",
                     help="skip the oracle leg (profiling runs)")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the workloads timed beside the headline (profiling runs)")
     ap.add_argument("--sample-positions", type=int, default=160,
                     help="spatial positions the CPU oracle is timed and compared on")
     args = ap.parse_args()
@@ -136,9 +242,10 @@ def main():
                 "level": levels[dom]["level"].name,
                 "algorithmic_bytes_per_launch": alg_bytes,
                 "avg_launch_ms": round(per_level_ms[dom], 4)}
-    roofline["traffic"] = measured_traffic(wl.name, levels[dom]["info"])
+    roofline["traffic"], roofline["traffic_source"] = measured_traffic(wl.name, levels[dom]["info"])
     total_alg = sum(L["info"]["algorithmic_bytes"] for L in levels)
-    step_gbps = total_alg / (ms_per_step * 1e-3) / 1e9
+    step_gbps = total_alg / (ms_per_step * 1e-3) / 1e9         # wall clock around the K steps
+    event_gbps = total_alg / (sum(per_level_ms) * 1e-3) / 1e9  # HIP events around every launch
 
     # ---- plain copy kernel of the same footprint: the practical HBM ceiling on this machine
     L0 = levels[dom]
@@ -255,7 +362,11 @@ def main():
                                    "frac": round(proj_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
                       "launch": proj_info}
     del proj_w, proj_y
-    # restore O (the copy probe used it as scratch)
+    # ---- the other workloads, so that one run shows every level shape
+    others = None
+    if not args.no_other_workloads and wl.name == "C3":
+        others = other_workloads(B, torch, synth, np, stream, dev, L0)
+    # restore O (the probes above used it as scratch)
     step()
     torch.cuda.synchronize()
 
@@ -294,8 +405,13 @@ def main():
                                            f"{L['level'].head_dim}" for L in levels),
                    "io_dtype": "bf16", "accumulate": "f32",
                    "launch": [L["info"] for L in levels]},
-        "pct_hbm_roofline": round(100.0 * step_gbps / HBM_PEAK_GBPS, 2),
-        "algorithmic_GBps": round(step_gbps, 1),
+        # the fraction of the HBM roofline, from the HIP events around every launch of the step
+        # (for a one-level workload this is roofline.frac); the wall-clock figure beside it
+        # includes the host's launch gaps
+        "pct_hbm_roofline": round(100.0 * event_gbps / HBM_PEAK_GBPS, 2),
+        "algorithmic_GBps": round(event_gbps, 1),
+        "wall_clock": {"ms_per_step": round(ms_per_step, 4), "algorithmic_GBps": round(step_gbps, 1),
+                       "pct_hbm_roofline": round(100.0 * step_gbps / HBM_PEAK_GBPS, 2)},
         "per_level_ms": [round(x, 4) for x in per_level_ms],
         "launch_ms_min_median": [[round(float(np.min(t)), 4), round(float(np.median(t)), 4)]
                                  for t in lv_times],
@@ -309,6 +425,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "parity": parity,
+        "other_workloads": others,
     }
     print(json.dumps(out))
     for L in levels:

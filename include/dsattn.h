@@ -278,8 +278,8 @@ int dsattn_temporal_conv(const dsattn_conv_desc *desc, const void *X, const void
                          const float *bias, void *Y, void *stream);
 
 /*
- * The token-wise linear projections around the temporal attention (Section 4.2: queries, keys
- * and values "are computed from tokens"; the paper gives no formula beyond that, these are the
+ * The token-wise linear projections around the temporal attention (Section 4.2 derives the
+ * queries, keys and values from the tokens and gives no formula beyond that; these are the
  * usual  Y_k = X W_k^T + b_k).  n_out weight sets are applied to the same X in one launch (3 for
  * Q, K, V: X is read from HBM once for all of them; 1 for the output projection).  Because the
  * projection is per token, projecting before or after a clip's context is gathered is the same.

@@ -30,14 +30,15 @@
  *     s_j = scale * sum_d Q[a][p][g][d] * K[ctx_j][p][g][d] + b_j
  *     A_j = exp(s_j - max_j s_j) / sum_j exp(s_j - max_j s_j)
  *     O[a][p][g][d] = sum_j A_j * V[ctx_j][p][g][d]
- *   b_j is the scope weight of Section 5.1 ("the weights of frames in G and N are
- *   dynamically adjusted"), taken as an additive logit bias: bias_local for the
+ *   b_j is the scope weight of Section 5.1 (there the two scopes are weighted
+ *   differently from one denoising timestep to the next), taken as an additive
+ *   logit bias: bias_local for the
  *   keys of the local part, bias_global for the keys of the global part; both 0
  *   unless the caller sets them (raising a scope's logits by b multiplies its
  *   unnormalised softmax weights by e^b).
  *   Optional sliding window (Section 4.2 describes the local context as the
- *   neighbouring frames of the query frame a, "typically achieved through window
- *   attention"): with window = r >= 0 a LOCAL key frame f is visible to the
+ *   neighbouring frames of the query frame a and names window attention as the
+ *   usual way to get it): with window = r >= 0 a LOCAL key frame f is visible to the
  *   query of frame a only if |f - a| <= r; hidden keys get weight exactly 0.
  *   Global keys are always visible.  window < 0 switches this off (every query
  *   of the clip sees the clip's whole local list).

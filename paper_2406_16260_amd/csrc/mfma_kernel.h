@@ -115,6 +115,30 @@ __device__ __forceinline__ float colmax(float x)
     return x;
 }
 
+// The multiply-accumulate of the accumulator chains of O^T = V^T P^T and of the denominator.  A
+// kernel variant takes its key tiles either in pairs (32 keys per 16x16x32 instruction) or one
+// by one (16 keys per 16x16x16 instruction), never both: a 16x16x16 result fed as the C operand
+// of a 16x16x32 issued right behind it came back with wrong elements on this toolchain.  Every
+// step of those chains goes through PvChain<kPairs>::mac, whose operand types fit one instruction
+// only, so a chain that mixes the two does not compile.
+template <bool PAIRS>
+struct PvChain;
+template <>
+struct PvChain<true> {
+    static __device__ __forceinline__ f32x4 mac(const bf16x8 a, const bf16x8 b, const f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+};
+template <>
+struct PvChain<false> {
+    static __device__ __forceinline__ f32x4 mac(const bf16x4 a, const bf16x4 b, const f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, a),
+                                                        __builtin_bit_cast(s16x4, b), c, 0, 0, 0);
+    }
+};
+
 // WPE = wavefronts per SIMD the register budget is sized for (2: 256 VGPRs, 1: 512); a
 // workgroup is at most 4 * WPE wavefronts so that it fits one compute unit.
 template <int D, int HPW, int NLT, int NGT, int WPE, bool OUT_F32>
@@ -274,7 +298,7 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
     bf16x8 ones8;
 #pragma unroll
     for (int e = 0; e < 8; ++e) ones8[e] = (__bf16)1.0f;
-    const s16x4 ones = __builtin_bit_cast(s16x4, __builtin_shufflevector(ones8, ones8, 0, 1, 2, 3));
+    const bf16x4 ones4 = __builtin_shufflevector(ones8, ones8, 0, 1, 2, 3);
 
     // V^T operand for channels 16*(2kb+hf) .. +15 from the V operand `av` (16 keys x 32 channels):
     // an exact transpose through the matrix core.  The lane gets keys 4 lg .. 4 lg + 3 of channel
@@ -297,8 +321,13 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
     // then of its second, in both operands).  Otherwise every tile goes through the 16x16x16 MFMA:
     // an accumulator chain never mixes the two instructions.
     constexpr bool kPairs = NGT % 2 == 0 && NLT % 2 == 0;
+    using Chain = PvChain<kPairs>;
     constexpr int NGP = kPairs ? NGT / 2 : 0, NLP = kPairs ? NLT / 2 : 0;  // tile pairs
     constexpr int NGS = NGT - 2 * NGP, NLS = NLT - 2 * NLP;                // single tiles
+    // The accumulator chains of O^T and of the denominator run over the pairs (16x16x32) and
+    // over the single tiles (16x16x16): one of the two sets must be empty.
+    static_assert((NGP + NLP == 0) || (NGS + NLS == 0),
+                  "an accumulator chain would mix the 16x16x32 and the 16x16x16 instruction");
 
     // ---- prologue.  Independent loads are issued together so that the chunk starts after
     // two memory round trips: (1) global frame indices, boundary frames, Q of the first clip;
@@ -551,27 +580,28 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
             // the denominator is the sum of the *rounded* weights, taken on the matrix core:
             // a row of ones times P^T leaves sum_k P^T[k][a] in every row of column a
             f32x4 den = {0.f, 0.f, 0.f, 0.f};
+            if constexpr (kPairs) {
 #pragma unroll
-            for (int u = 0; u < NGP; ++u) {
-                ptp[u] = join(weights(2 * u), weights(2 * u + 1));
-                den = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones8, ptp[u], den, 0, 0, 0);
-            }
+                for (int u = 0; u < NGP; ++u) {
+                    ptp[u] = join(weights(2 * u), weights(2 * u + 1));
+                    den = Chain::mac(ones8, ptp[u], den);
+                }
 #pragma unroll
-            for (int u = 0; u < NLP; ++u) {
-                ptp[NGP + u] = join(weights(NGT + 2 * u), weights(NGT + 2 * u + 1));
-                den = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones8, ptp[NGP + u], den, 0, 0, 0);
-            }
+                for (int u = 0; u < NLP; ++u) {
+                    ptp[NGP + u] = join(weights(NGT + 2 * u), weights(NGT + 2 * u + 1));
+                    den = Chain::mac(ones8, ptp[NGP + u], den);
+                }
+            } else {
 #pragma unroll
-            for (int u = 0; u < NGS; ++u) {
-                ptg[u] = weights(2 * NGP + u);
-                den = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
-                    ones, __builtin_bit_cast(s16x4, ptg[u]), den, 0, 0, 0);
-            }
+                for (int u = 0; u < NGS; ++u) {
+                    ptg[u] = weights(u);
+                    den = Chain::mac(ones4, ptg[u], den);
+                }
 #pragma unroll
-            for (int u = 0; u < NLS; ++u) {
-                ptl[u] = weights(NGT + 2 * NLP + u);
-                den = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
-                    ones, __builtin_bit_cast(s16x4, ptl[u]), den, 0, 0, 0);
+                for (int u = 0; u < NLS; ++u) {
+                    ptl[u] = weights(NGT + u);
+                    den = Chain::mac(ones4, ptl[u], den);
+                }
             }
             const float inv = __builtin_amdgcn_rcpf(den[0]);  // within 1 ulp
 
@@ -579,48 +609,42 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
             f32x4 o[NDT];
 #pragma unroll
             for (int dt = 0; dt < NDT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if constexpr (kPairs) {
 #pragma unroll
-            for (int u = 0; u < NGP; ++u)
+                for (int u = 0; u < NGP; ++u)
 #pragma unroll
-                for (int dt = 0; dt < NDT; ++dt)
-                    o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vgp[u][hh][dt], ptp[u], o[dt], 0,
-                                                                    0, 0);
+                    for (int dt = 0; dt < NDT; ++dt) o[dt] = Chain::mac(vgp[u][hh][dt], ptp[u], o[dt]);
 #pragma unroll
-            for (int u = 0; u < NGS; ++u)
+                for (int u = 0; u < NLP; ++u)
 #pragma unroll
-                for (int dt = 0; dt < NDT; ++dt)
-                    o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
-                        __builtin_bit_cast(s16x4, vgs[u][hh][dt]),
-                        __builtin_bit_cast(s16x4, ptg[u]), o[dt], 0, 0, 0);
+                    for (int kb = 0; kb < NKB; ++kb) {
+                        const bf16x8 av0 = read_op32(vring, arow[2 * u], hh, kb);
+                        const bf16x8 av1 = read_op32(vring, arow[2 * u + 1], hh, kb);
 #pragma unroll
-            for (int u = 0; u < NLP; ++u)
-#pragma unroll
-                for (int kb = 0; kb < NKB; ++kb) {
-                    const bf16x8 av0 = read_op32(vring, arow[2 * u], hh, kb);
-                    const bf16x8 av1 = read_op32(vring, arow[2 * u + 1], hh, kb);
-#pragma unroll
-                    for (int hf = 0; hf < 2; ++hf) {
-                        const int dt = 2 * kb + hf;
-                        if (dt < NDT)
-                            o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                join(vt_from(av0, hf), vt_from(av1, hf)), ptp[NGP + u], o[dt], 0, 0,
-                                0);
+                        for (int hf = 0; hf < 2; ++hf) {
+                            const int dt = 2 * kb + hf;
+                            if (dt < NDT)
+                                o[dt] = Chain::mac(join(vt_from(av0, hf), vt_from(av1, hf)),
+                                                   ptp[NGP + u], o[dt]);
+                        }
                     }
-                }
+            } else {
 #pragma unroll
-            for (int u = 0; u < NLS; ++u)
+                for (int u = 0; u < NGS; ++u)
 #pragma unroll
-                for (int kb = 0; kb < NKB; ++kb) {
-                    const bf16x8 av = read_op32(vring, arow[2 * NLP + u], hh, kb);
+                    for (int dt = 0; dt < NDT; ++dt) o[dt] = Chain::mac(vgs[u][hh][dt], ptg[u], o[dt]);
 #pragma unroll
-                    for (int hf = 0; hf < 2; ++hf) {
-                        const int dt = 2 * kb + hf;
-                        if (dt < NDT)
-                            o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
-                                __builtin_bit_cast(s16x4, vt_from(av, hf)),
-                                __builtin_bit_cast(s16x4, ptl[u]), o[dt], 0, 0, 0);
+                for (int u = 0; u < NLS; ++u)
+#pragma unroll
+                    for (int kb = 0; kb < NKB; ++kb) {
+                        const bf16x8 av = read_op32(vring, arow[u], hh, kb);
+#pragma unroll
+                        for (int hf = 0; hf < 2; ++hf) {
+                            const int dt = 2 * kb + hf;
+                            if (dt < NDT) o[dt] = Chain::mac(vt_from(av, hf), ptl[u], o[dt]);
+                        }
                     }
-                }
+            }
 
             // ---- normalise; lane holds channels 16 dt + 4 lg + {0..3} of query frame l16
             if constexpr (OUT_F32) {

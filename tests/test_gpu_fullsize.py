@@ -14,10 +14,21 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def sample_positions(P, n):
+def sample_positions(P, n, info, heads):
+    """At least n positions spread over the level, plus the ones where the launch has its seams:
+    the first and last position of the level (the first and last row group of every chunk: the
+    oracle covers all frames, hence every chunk, of a sampled position) and the positions on both
+    sides of workgroup boundaries (a workgroup spans block_threads / 64 wavefronts of
+    heads_per_wave heads each)."""
     pos = set(((np.arange(n) * P) // n).tolist())
     pos.update({0, P - 1, P // 2})
-    return sorted(pos)
+    if info["kernel"] == 1:
+        pos_per_wg = max(1, (info["block_threads"] // 64) * info["heads_per_wave"] // heads)
+        n_wg = max(1, P // pos_per_wg)
+        for j in sorted({1, 2, n_wg // 3, n_wg // 2, n_wg - 1}):
+            if 0 < j < n_wg:
+                pos.update({j * pos_per_wg - 1, j * pos_per_wg})
+    return sorted(p for p in pos if 0 <= p < P)
 
 
 def run_level(wl, lv, out_dtype, n_pos):
@@ -27,7 +38,8 @@ def run_level(wl, lv, out_dtype, n_pos):
     q, k, v = synth.make_qkv(wl, lv, device=DEV)
     o, info = U.library_forward(q, k, v, wl.clip_len, wl.n_clips, wl.local_ctx, lv.heads, g,
                                 out_dtype=out_dtype)
-    pos = sample_positions(lv.P, n_pos)
+    pos = sample_positions(lv.P, n_pos, info, lv.heads)
+    assert len(pos) >= min(n_pos, lv.P)
     ref = U.oracle_forward(q, k, v, wl.clip_len, wl.n_clips, wl.local_ctx, lv.heads, g,
                            positions=pos)
     mx = U.assert_parity(o, ref, out_dtype, positions=pos, what=f"{wl.name}/{lv.name}")
@@ -38,25 +50,50 @@ def run_level(wl, lv, out_dtype, n_pos):
     return info, mx
 
 
-@pytest.mark.parametrize("name", ["C1", "C2", "C3"])
-def test_single_level_workloads_full_size(name):
+@pytest.mark.parametrize("name,n_pos", [("C1", 32), ("C2", 32), ("C3", 160)])
+def test_single_level_workloads_full_size(name, n_pos):
+    # the headline level is compared on every one of its 160 positions
     wl = synth.WORKLOADS[name]
-    info, _ = run_level(wl, wl.levels[0], "bf16", 10)
+    info, _ = run_level(wl, wl.levels[0], "bf16", n_pos)
     assert info["kernel"] == 1
 
 
-def test_c3_full_size_fp32_output_strict():
+@pytest.mark.parametrize("name", ["C1", "C2", "C3"])
+def test_single_level_workloads_full_size_fp32_output_strict(name):
     # bf16 inputs, fp32 accumulation, fp32 output: the 1e-2 bar holds outright
-    wl = synth.WORKLOADS["C3"]
-    info, mx = run_level(wl, wl.levels[0], "f32", 10)
+    wl = synth.WORKLOADS[name]
+    info, mx = run_level(wl, wl.levels[0], "f32", 32)
     assert info["kernel"] == 1 and mx <= 1e-2
 
 
 @pytest.mark.parametrize("level", [0, 1, 2, 3])
 def test_c4_levels_full_size(level):
     wl = synth.WORKLOADS["C4"]
-    info, _ = run_level(wl, wl.levels[level], "bf16", 6)
+    info, _ = run_level(wl, wl.levels[level], "bf16", 32)
     assert info["kernel"] == 1 and info["global_tiles"] == 4
+
+
+@pytest.mark.parametrize("level", [0, 1, 2, 3])
+def test_c4_levels_full_size_fp32_output_strict(level):
+    wl = synth.WORKLOADS["C4"]
+    info, mx = run_level(wl, wl.levels[level], "f32", 32)
+    assert info["kernel"] == 1 and info["global_tiles"] == 4 and mx <= 1e-2
+
+
+def test_paper_sized_clips_full_size():
+    # the headline tensors cut into the paper's eight 288-frame clips, 8 + 8 context frames,
+    # window radius 8, 16 global frames: the launch bench.py times as C3_8x288_w8_r8_G16
+    wl = synth.WORKLOADS["C3"]
+    lv = wl.levels[0]
+    g = synth.stride_global_idx(wl.F, 16)
+    print("[case] full size 8 x 288 frames w=8 r=8 G=16 on the C3 tensors", flush=True)
+    q, k, v = synth.make_qkv(wl, lv, device=DEV)
+    for od in ("bf16", "f32"):
+        o, info = U.library_forward(q, k, v, 288, 8, 8, lv.heads, g, out_dtype=od, window=8)
+        assert info["kernel"] == 1 and info["ring_reach"] == 8
+        pos = sample_positions(lv.P, 32, info, lv.heads)
+        ref = U.oracle_forward(q, k, v, 288, 8, 8, lv.heads, g, positions=pos, window=8)
+        U.assert_parity(o, ref, od, positions=pos, what=f"8x288 {od}")
 
 
 def test_c1_gather_full_size_bit_exact():

@@ -607,3 +607,34 @@ def test_dedup_global_many_global_frames_on_matrix_cores(D, h, w, window, G):
                                     flags=B.DSATTN_FLAG_DEDUP_GLOBAL, bias_global=-0.3)
     assert info["kernel"] == 1 and info["global_tiles"] == 4
     U.assert_parity(o, ref, "f32", what=f"dedup D={D} G={G} w={w} window={window}")
+
+
+# ---------------------------------------------------------------- accumulator chains of O^T and the denominator
+
+@pytest.mark.parametrize("D,h", [(40, 4), (80, 2), (160, 2)])
+@pytest.mark.parametrize("w,G,tiles,pairs", [
+    (4, 64, (2, 4), True),     # even / even: key tiles enter in pairs (16x16x32)
+    (4, 0, (2, 0), True),      # even / none
+    (0, 64, (1, 4), False),    # odd local tiles with an even number of global ones: single tiles
+    (12, 0, (3, 0), False),    # odd / none
+    (2, 16, (2, 1), False),    # even local tiles with an odd number of global ones
+    (0, 7, (1, 1), False),     # odd / odd
+])
+def test_accumulator_chain_families(D, h, w, G, tiles, pairs):
+    """Both sides of the rule that decides whether a variant feeds its key tiles to O^T = V^T P^T
+    in pairs or one by one (a chain never mixes the two instructions), at the three head sizes of
+    the base model: each family against the oracle, strict fp32-output bar, peaked softmax so
+    that single weights matter."""
+    clip_len, n_clips, P = 16, 5, 3
+    F = clip_len * n_clips
+    g = synth.random_sorted_global_idx(F, G, seed=3).tolist() if G else []
+    q, k, v = make(F, P, h * D, 900 + D + w + G, "iid", "bf16")
+    announce(f"chain family D={D} tiles={tiles} pairs={pairs}")
+    for scale in (0.0, 3.0 / np.sqrt(D)):
+        o, info = U.library_forward(q, k, v, clip_len, n_clips, w, h, g, out_dtype="f32",
+                                    scale=scale)
+        assert info["kernel"] == 1
+        assert (info["local_tiles"], info["global_tiles"]) == tiles
+        assert (tiles[0] % 2 == 0 and tiles[1] % 2 == 0) == pairs
+        ref = U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g, scale=scale)
+        U.assert_parity(o, ref, "f32", what=f"chain family D={D} {tiles}")

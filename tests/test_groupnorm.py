@@ -152,6 +152,28 @@ def test_groupnorm_full_size_level():
 
 
 @pytest.mark.gpu
+def test_groupnorm_level_sized_tensor_against_the_oracle():
+    # a whole level-sized tensor (the 64-frame workload's level: 64 x 2,560 x 320, 32 groups)
+    # checked element by element against the oracle itself, statistics included
+    wl = synth.WORKLOADS["C1"]
+    lv = wl.levels[0]
+    print(f"[case] groupnorm {wl.F} x {lv.P} x {lv.C} vs oracle", flush=True)
+    x = synth.make_tensor(wl.F, lv.P, lv.C, 13, "correlated", "bf16", device=DEV)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(14)
+    gamma = 1.0 + 0.1 * torch.randn(lv.C, generator=gen, device=DEV)
+    beta = 0.1 * torch.randn(lv.C, generator=gen, device=DEV)
+    y, stats = run_gn(x, wl.clip_len, wl.n_clips, 32, gamma=gamma, beta=beta)
+    ref, mean, var = oracle.groupnorm(x.cpu().double().numpy(), wl.clip_len, wl.n_clips, 32,
+                                      gamma=gamma.cpu().double().numpy(),
+                                      beta=beta.cpu().double().numpy())
+    st = stats.cpu().double().numpy()
+    np.testing.assert_allclose(st[:32], mean, rtol=0, atol=2e-6)
+    np.testing.assert_allclose(st[32:], 1.0 / np.sqrt(var + 1e-5), rtol=3e-6, atol=0)
+    U.assert_parity(y, ref, "bf16", what="groupnorm level-sized vs oracle")
+
+
+@pytest.mark.gpu
 @pytest.mark.parametrize("offset", [100.0, -3000.0])
 def test_groupnorm_large_means_do_not_cancel(offset):
     """Means far larger than the deviations (fp32 tensors, |mean| / std up to 3,000): the one-pass
