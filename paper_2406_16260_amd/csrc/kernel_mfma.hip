@@ -127,7 +127,8 @@ bool mfma_plan(dsattn_plan_t &pl)
     // where the workgroups run in rounds of `slots`.  With few rounds the workgroups stay in
     // step and a last round less than 85 % full costs a whole round; after about six rounds they have
     // drifted apart and the tail costs little more than its share.  Fewer workgroups than slots
-    // leave compute units idle.
+    // leave compute units idle.  Every chunk also pays for its start, which decides short videos
+    // (four clips: one chunk per row group beats two).
     const double slots = (double)kCus * blocks_cu;
     int best_nc = 1;
     double best_cost = 1e300;
@@ -146,7 +147,8 @@ bool mfma_plan(dsattn_plan_t &pl)
                                                 : 0.0);
         const double fill = rounds_eff / rounds;
         const double kv = (16.0 * m + (nc > 1 ? 2.0 * wr : 0.0) + G) / (16.0 * m);
-        const double cost = (2.0 + 2.0 * kv) / 4.0 * fill;
+        // a chunk's start (two memory round trips before its first tile) costs about one tile
+        const double cost = (2.0 + 2.0 * kv) / 4.0 * fill * (1.0 + 1.0 / m);
         if (cost < best_cost - 1e-12) {
             best_cost = cost;
             best_nc = nc;

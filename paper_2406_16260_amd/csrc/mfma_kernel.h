@@ -157,7 +157,10 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int R = a.R;
     const int lane = threadIdx.x & 63;
-    const int wv = threadIdx.x >> 6;
+    // (readfirstlane tells the compiler that everything derived from the wavefront's index is
+    // uniform: the row group's base pointers and the buffer descriptors then live in scalar
+    // registers)
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int WPB = blockDim.x >> 6;
     unsigned char *kring = smem + wv * ((2 * R + 16) * RS);
     unsigned char *vring = kring + R * RS;
@@ -220,12 +223,19 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
     };
 
     // 16 consecutive frames starting at frame0 (wave-uniform); rows >= nrows and frames
-    // outside [lo, hi) give zeros
+    // outside [lo, hi) give zeros.  A tile that lies inside [lo, hi) is read with plain loads.
+    // Any other is read through a buffer descriptor that covers exactly the frames that may be
+    // read: it starts at the first such frame and ends with the last, so a lane whose row lies
+    // before (its offset wraps to a huge unsigned value; 16 frame rows span less than 2^32
+    // bytes) or after gets zeros from the hardware's range check, with no per-lane test and no
+    // branch per load (the tiles at the ends of the video and of a clip's slab, which are every
+    // other tile of a short video); no frame readable: loads that touch no memory.
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    constexpr uint32_t kOob = 0xfffffff0u;
     auto load_rows = [&](const unsigned char *base, int frame0, int nrows, int lo, int hi,
                          uint4(&st)[NLD]) __attribute__((always_inline)) {
-        const unsigned char *tb = base + (int64_t)frame0 * FSB;
         if (nrows == 16 && frame0 >= lo && frame0 + 16 <= hi) {
-            // whole tile inside the video: no per-lane frame checks
+            const unsigned char *tb = base + (int64_t)frame0 * FSB;
 #pragma unroll
             for (int r = 0; r < NLD; ++r) {
                 if (kFullTile || r + 1 < NLD) {
@@ -237,13 +247,19 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
                 }
             }
         } else {
+            const int bf = max(frame0, lo);          // first frame that may be read
+            const int hv = min(hi, frame0 + nrows);  // one past the last
+            const uint32_t delta = (uint32_t)(bf - frame0) * (uint32_t)FSB;
+            const int64_t span = (int64_t)(hv - bf) * FSB;
+            const uint32_t nrec = span > 0 ? (uint32_t)span : 0u;
+            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+                (void *)(base + (int64_t)(nrec ? bf : 0) * FSB), 0, (int)nrec, 0x00020000);
 #pragma unroll
             for (int r = 0; r < NLD; ++r) {
-                const int f = frame0 + fq[r];
-                const bool ok = in_tile(r) && fq[r] < nrows && f >= lo && f < hi;
-                uint4 x = make_uint4(0, 0, 0, 0);
-                if (ok) x = *(const uint4 *)(tb + voff[r]);
-                st[r] = x;
+                uint32_t off = voff[r] - delta;
+                if (!(kFullTile || r + 1 < NLD)) off = in_tile(r) ? off : kOob;
+                const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0);
+                st[r] = make_uint4(x[0], x[1], x[2], x[3]);
             }
         }
     };
@@ -335,6 +351,9 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
     bf16x8 kg[NGT > 0 ? NGT : 1][HPW][NKB];
     bf16x8 vgp[NGP > 0 ? NGP : 1][HPW][NDT];  // V^T of the global tile pairs
     bf16x4 vgs[NGS > 0 ? NGS : 1][HPW][NDT];  // V^T of the single global tiles
+    // Rows on their way from memory: a tile's rows are asked for one tile ahead of their use.
+    // (Asking two tiles ahead, with a second register set where a wavefront has a whole SIMD's
+    // registers, was measured and changed nothing: the kernel is not short of loads in flight.)
     uint4 stQ[NLD], stK[NLD], stV[NLD];
     uint4 gK[NLD], gV[NLD];
 
@@ -450,11 +469,11 @@ __global__ __launch_bounds__(256 * WPE, WPE) void dsattn_mfma_kernel(const MfmaA
         store_tile(qo, 0, 16, stQ);
         store_tile(kring, s_bulk, R, stK);
         store_tile(vring, s_bulk, R, stV);
-        if (i + 1 < c1) {
-            load_rows(Qb, 16 * (i + 1), 16, 0, F, stQ);
-            load_rows(Kb, 16 * (i + 1) + w, 16, flo, fhi, stK);
-            load_rows(Vb, 16 * (i + 1) + w, 16, flo, fhi, stV);
-        }
+        // (past the chunk's last tile: zero rows, loads that touch no memory)
+        const int nnext = i + 1 < c1 ? 16 : 0;
+        load_rows(Qb, 16 * (i + 1), nnext, 0, F, stQ);
+        load_rows(Kb, 16 * (i + 1) + w, nnext, flo, fhi, stK);
+        load_rows(Vb, 16 * (i + 1) + w, nnext, flo, fhi, stV);
         wave_sync();
 
         // validity of this lane's local keys: C/D row 4*lg + e of local tile tl is ring slot

@@ -153,9 +153,17 @@ __global__ __launch_bounds__(64 * WVM * WVN, WVM * WVN / 4) void tconv_mfma_kern
     // so that the X lines they share (the same rows, shifted by P per tap) are still in L2.
     // Past the last stage every lane of the loads is an out-of-range one: no traffic, the same
     // number of loads in flight, and no branch inside the multiply schedule.
+    // The calls come with ks = 0, 1, 2, ... in order, so the channel block and the tap are
+    // counted along instead of being divided out of ks (a scalar division is some forty
+    // instructions, and they would sit between two matrix instructions).
+    const int taps = 2 * a.n + 1;
+    int su_kc = 0, su_t = 0;
     auto stage_setup = [&](int ks) __attribute__((always_inline)) {
-        const int taps = 2 * a.n + 1;
-        const int kc = ks / taps, t = ks - kc * taps;
+        const int kc = su_kc, t = su_t;
+        if (++su_t == taps) {
+            su_t = 0;
+            ++su_kc;
+        }
         ld_live = ks < a.KS && kc * kBK + lc * 8 < a.Cin;  // c_in % 8 == 0: a chunk is all in or out
         const int64_t mshift = m0 + (int64_t)(t - a.n) * a.P;  // video row of tile row 0 at this tap
         ld_xstep = (uint32_t)((int)(mshift - rb) * rowbytes + kc * (kBK * 2));
@@ -284,11 +292,12 @@ __global__ __launch_bounds__(64 * WVM * WVN, WVM * WVN / 4) void tconv_mfma_kern
         // loads of the stage after it interleaved with the other half.  After the last stage
         // those fragments are never used: the reads stay in bounds, and keeping them
         // unconditional keeps the multiplies out of divergent control flow.
+        // (the addresses of the stage after next are worked out before the barrier, under the
+        // multiplies: every load of stage ks + 1 has been issued by now, see kSpread)
+        stage_setup(ks + 2);
         mma_range((NKK - 1) & 1, 0, NM / 2, false, bufc, 0, TAIL + (NKK - 1) * NM);
         __builtin_amdgcn_s_waitcnt(0);
         __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-        stage_setup(ks + 2);
         __builtin_amdgcn_sched_barrier(0);
         mma_range((NKK - 1) & 1, NM / 2, NM, true, bufn, 0, 0);
     }
