@@ -55,9 +55,10 @@ bool mfma_plan(dsattn_plan_t &pl)
     // the kernel addresses the 16 frame rows of a tile with 32-bit byte offsets
     if ((int64_t)d.spatial * pl.C * 2 * 16 >= ((int64_t)1 << 32)) return false;
     const int G = (int)pl.global_idx.size();
-    // global key tiles: variants exist for 0, 1 and 4 tiles; a partly used tile is masked
-    if (G > 64) return false;
-    const int NGT = G == 0 ? 0 : (G <= 16 ? 1 : 4);
+    // global key tiles: variants exist for 0, 1, 4 and (where a wavefront's registers hold
+    // them) 8 tiles; a partly used tile is masked
+    if (G > 128) return false;
+    const int NGT = G == 0 ? 0 : (G <= 16 ? 1 : (G <= 64 ? 4 : 8));
     // Frames a tile's local scope can reach beyond the tile on each side: up to the end of the
     // clip's local range (the rest of the clip plus the neighbour's context frames), or the
     // sliding window's radius when that is shorter.  With 16-frame clips and no window this is
@@ -77,6 +78,8 @@ bool mfma_plan(dsattn_plan_t &pl)
     // The set-union option is built into the variants with one global key tile, and into the
     // four-tile variants that run one wavefront per SIMD (head_dim 160 and 128): with that option
     // and four tiles only those are candidates.
+    // With eight tiles it is not built in (the generic kernel takes those).
+    if ((d.flags & DSATTN_FLAG_DEDUP_GLOBAL) && NGT == 8) return false;
     const bool need_wpe1 = (d.flags & DSATTN_FLAG_DEDUP_GLOBAL) && NGT == 4;
     const MfmaVariant *var = nullptr;
     int var_id = -1;

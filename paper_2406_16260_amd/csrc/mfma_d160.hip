@@ -8,6 +8,8 @@ static const MfmaVariant kVariantsD160[] = {
     DSATTN_MFMA_SET(160, 1, 2),  // 1 head(s) per wavefront: rows of 160 channels
     // up to 64 global frames: four global key tiles held in registers
     DSATTN_MFMA_SET_G4(160, 1, 1),
+    // (eight global key tiles do not fit a wavefront's registers at this head size: 65 to 128
+    // global frames run the generic kernel)
 };
 
 const MfmaVariant *mfma_variants_d160(int *n)

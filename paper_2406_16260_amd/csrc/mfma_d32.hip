@@ -11,6 +11,8 @@ static const MfmaVariant kVariantsD32[] = {
     // up to 64 global frames: four global key tiles held in registers
     DSATTN_MFMA_SET_G4(32, 2, 2),
     DSATTN_MFMA_SET_G4(32, 1, 2),
+    // up to 128 global frames: eight global key tiles held in registers
+    DSATTN_MFMA_SET_G8(32, 1, 2),
 };
 
 const MfmaVariant *mfma_variants_d32(int *n)

@@ -11,6 +11,9 @@ static const MfmaVariant kVariantsD40[] = {
     // up to 64 global frames: four global key tiles held in registers
     DSATTN_MFMA_SET_G4(40, 2, 2),
     DSATTN_MFMA_SET_G4(40, 1, 2),
+    // up to 128 global frames: eight global key tiles held in registers
+    DSATTN_MFMA_SET_G8(40, 2, 1),
+    DSATTN_MFMA_VARIANT(40, 1, 1, 8, 2), DSATTN_MFMA_VARIANT(40, 1, 2, 8, 2),
 };
 
 const MfmaVariant *mfma_variants_d40(int *n)

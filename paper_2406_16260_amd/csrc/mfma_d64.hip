@@ -9,6 +9,8 @@ static const MfmaVariant kVariantsD64[] = {
     DSATTN_MFMA_SET(64, 1, 2),  // 1 head(s) per wavefront: rows of 64 channels
     // up to 64 global frames: four global key tiles held in registers
     DSATTN_MFMA_SET_G4(64, 1, 2),
+    // up to 128 global frames: eight global key tiles held in registers
+    DSATTN_MFMA_SET_G8(64, 1, 1),
 };
 
 const MfmaVariant *mfma_variants_d64(int *n)

@@ -9,6 +9,8 @@ static const MfmaVariant kVariantsD80[] = {
     DSATTN_MFMA_SET(80, 1, 2),  // 1 head(s) per wavefront: rows of 80 channels
     // up to 64 global frames: four global key tiles held in registers
     DSATTN_MFMA_SET_G4(80, 1, 2),
+    // up to 128 global frames: eight global key tiles held in registers
+    DSATTN_MFMA_SET_G8(80, 1, 1),
 };
 
 const MfmaVariant *mfma_variants_d80(int *n)

@@ -9,6 +9,8 @@ static const MfmaVariant kVariantsD96[] = {
     DSATTN_MFMA_SET(96, 1, 2),  // 1 head(s) per wavefront: rows of 96 channels
     // up to 64 global frames: four global key tiles held in registers
     DSATTN_MFMA_SET_G4(96, 1, 2),
+    // up to 128 global frames: eight global key tiles held in registers
+    DSATTN_MFMA_SET_G8(96, 1, 1),
 };
 
 const MfmaVariant *mfma_variants_d96(int *n)

@@ -726,8 +726,14 @@ const MfmaVariant *mfma_variants_d32(int *n);
     DSATTN_MFMA_VARIANT(D, HPW, 2, 0, WPE), DSATTN_MFMA_VARIANT(D, HPW, 2, 1, WPE),            \
     DSATTN_MFMA_VARIANT(D, HPW, 3, 0, WPE), DSATTN_MFMA_VARIANT(D, HPW, 3, 1, WPE)
 
-// four global key tiles, local context 0..8 frames
+// four global key tiles, local context 0..16 frames
 #define DSATTN_MFMA_SET_G4(D, HPW, WPE)                                                        \
-    DSATTN_MFMA_VARIANT(D, HPW, 1, 4, WPE), DSATTN_MFMA_VARIANT(D, HPW, 2, 4, WPE)
+    DSATTN_MFMA_VARIANT(D, HPW, 1, 4, WPE), DSATTN_MFMA_VARIANT(D, HPW, 2, 4, WPE),            \
+    DSATTN_MFMA_VARIANT(D, HPW, 3, 4, WPE)
+
+// eight global key tiles (up to 128 global frames), local context 0..16 frames
+#define DSATTN_MFMA_SET_G8(D, HPW, WPE)                                                        \
+    DSATTN_MFMA_VARIANT(D, HPW, 1, 8, WPE), DSATTN_MFMA_VARIANT(D, HPW, 2, 8, WPE),            \
+    DSATTN_MFMA_VARIANT(D, HPW, 3, 8, WPE)
 
 }  // namespace dsattn

@@ -536,11 +536,11 @@ def test_randomised_shapes_against_oracle():
                                     window=window, bias_global=bg)
         # MFMA variants: clips of whole 16-frame tiles, head_dim 32/40/64/80/96/128/160 with any
         # head count; the frames a tile's local scope reaches beyond the tile (the window radius,
-        # at most the rest of the clip's local range) <= 16 with up to 16 global frames, <= 8
-        # with 17..64
+        # at most the rest of the clip's local range) <= 16; up to 64 global frames (the sweep
+        # draws no more)
         reach = clip_len - 16 + w
         reach = reach if window is None else min(window, reach)
-        expect_mfma = clip_len % 16 == 0 and D != 24 and (reach <= 16 if G <= 16 else reach <= 8)
+        expect_mfma = clip_len % 16 == 0 and D != 24 and reach <= 16
         assert info["kernel"] == (1 if expect_mfma else 0), (info, case)
         U.assert_parity(o, ref, "f32", what=f"random case {case}")
 
@@ -638,3 +638,44 @@ def test_accumulator_chain_families(D, h, w, G, tiles, pairs):
         assert (tiles[0] % 2 == 0 and tiles[1] % 2 == 0) == pairs
         ref = U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g, scale=scale)
         U.assert_parity(o, ref, "f32", what=f"chain family D={D} {tiles}")
+
+
+# ---------------------------------------------------------------- wide contexts: 16 local frames with 17..64 global, 65..128 global
+
+@pytest.mark.parametrize("D,h,w,G,tiles", [
+    (160, 2, 16, 64, (3, 4)), (160, 2, 9, 17, (3, 4)), (80, 4, 12, 40, (3, 4)), (40, 8, 16, 64, (3, 4)),
+    (40, 3, 10, 33, (3, 4)), (128, 2, 16, 64, (3, 4)), (96, 2, 16, 20, (3, 4)), (64, 2, 11, 64, (3, 4)),
+    (32, 4, 16, 64, (3, 4)),
+    # 65 to 128 global frames: eight global key tiles
+    (80, 4, 4, 128, (2, 8)), (80, 2, 16, 100, (3, 8)), (40, 8, 4, 128, (2, 8)), (40, 3, 2, 65, (2, 8)),
+    (96, 2, 8, 128, (2, 8)), (64, 2, 16, 128, (3, 8)), (32, 4, 0, 90, (1, 8)), (128, 2, 0, 128, (1, 8)),
+])
+def test_wide_contexts_on_matrix_cores(D, h, w, G, tiles):
+    clip_len, n_clips, P = 16, 10, 3
+    F = clip_len * n_clips
+    g = np.random.default_rng(G + D).integers(0, F, size=G).tolist()   # repeats allowed
+    q, k, v = make(F, P, h * D, 1200 + D + w + G, "iid", "bf16")
+    announce(f"wide context D={D} h={h} w={w} G={G}")
+    for od, scale in (("f32", 0.0), ("bf16", 2.0 / np.sqrt(D))):
+        o, info = U.library_forward(q, k, v, clip_len, n_clips, w, h, g, out_dtype=od, scale=scale)
+        assert info["kernel"] == 1 and (info["local_tiles"], info["global_tiles"]) == tiles, info
+        ref = U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g, scale=scale)
+        U.assert_parity(o, ref, od, what=f"wide context D={D} w={w} G={G}")
+
+
+def test_contexts_beyond_the_matrix_core_variants_run_the_generic_kernel():
+    q, k, v = make(64, 2, 2 * 160, 1300, "iid", "bf16")
+    for D, h, w, G in ((160, 2, 4, 65), (128, 2, 4, 70), (80, 4, 4, 129)):
+        g = list(range(G % 64)) + list(range(64)) + ([5] * (G - 64 - G % 64) if G > 64 + G % 64 else [])
+        g = (g + [0] * G)[:G]
+        o, info = U.library_forward(q, k, v, 16, 4, w, h, g, out_dtype="f32")
+        assert info["kernel"] == 0, (D, G, info)
+        ref = U.oracle_forward(q, k, v, 16, 4, w, h, g)
+        U.assert_parity(o, ref, "f32", what=f"generic D={D} G={G}")
+    # the set union with more than 64 global frames
+    g = list(range(64)) + list(range(30))
+    o, info = U.library_forward(q, k, v, 16, 4, 2, 4, g, out_dtype="f32",
+                                flags=B.DSATTN_FLAG_DEDUP_GLOBAL)
+    assert info["kernel"] == 0
+    ref = U.oracle_forward(q, k, v, 16, 4, 2, 4, g, dedup=True)
+    U.assert_parity(o, ref, "f32", what="dedup G=94")
