@@ -361,7 +361,51 @@ def main():
                                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                    "frac": round(proj_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
                       "launch": proj_info}
-    del proj_w, proj_y
+    # ---- the whole temporal-attention layer around the kernel (Section 4.2): X -> (Q, K, V) in
+    # one launch -> Dual-scope attention -> output projection, back to back on one stream, timed
+    # as one interval beside the sum of its separately timed parts; and the vendor library's GEMM
+    # on the same tokens and weights (through torch.matmul) as the yardstick of the projections
+    wo = synth.make_conv_weights(1, lvl.C, lvl.C, wl.seed + 70, "bf16", device=dev)[0].reshape(lvl.C, lvl.C)
+    yo = torch.empty_like(L0["q"])
+
+    def outproj():
+        B.dsattn_linear(rows, lvl.C, lvl.C, L0["o"], [wo], [yo], stream=stream)
+
+    def layer():
+        B.dsattn_linear(rows, lvl.C, lvl.C, L0["q"], proj_w, proj_y, stream=stream)
+        B.dsattn_forward(L0["plan"], proj_y[0], proj_y[1], proj_y[2], L0["o"], stream)
+        B.dsattn_linear(rows, lvl.C, lvl.C, L0["o"], [wo], [yo], stream=stream)
+
+    def timed(fn, reps=5):
+        fn()
+        g0.record(stream)
+        for _ in range(reps):
+            fn()
+        g1.record(stream)
+        torch.cuda.synchronize()
+        return g0.elapsed_time(g1) / reps
+    outproj_ms = timed(outproj)
+    layer_ms = timed(layer)
+    attn_ms = timed(lambda: B.dsattn_forward(L0["plan"], proj_y[0], proj_y[1], proj_y[2], L0["o"], stream))
+    proj_flops1 = 2.0 * rows * lvl.C * lvl.C
+    wcat = torch.cat(proj_w, 0).contiguous()
+    vendor_qkv_ms = timed(lambda: torch.matmul(L0["q"].view(rows, lvl.C), wcat.t()))
+    vendor_one_ms = timed(lambda: torch.matmul(L0["q"].view(rows, lvl.C), wo.t()))
+    temporal_layer = {
+        "ms": round(layer_ms, 4),
+        "parts_ms": {"qkv_projection": round(proj_ms, 4), "attention": round(attn_ms, 4),
+                     "output_projection": round(outproj_ms, 4)},
+        "sum_of_parts_ms": round(proj_ms + attn_ms + outproj_ms, 4),
+        "output_projection_TFLOPps": round(proj_flops1 / outproj_ms / 1e9, 1),
+        "vendor_gemm_yardstick": {
+            "what": "torch.matmul (the vendor library) on the same tokens and weights; context, "
+                    "not part of the path",
+            "qkv_as_one_gemm_ms": round(vendor_qkv_ms, 4),
+            "qkv_as_one_gemm_TFLOPps": round(3 * proj_flops1 / vendor_qkv_ms / 1e9, 1),
+            "one_projection_ms": round(vendor_one_ms, 4),
+            "one_projection_TFLOPps": round(proj_flops1 / vendor_one_ms / 1e9, 1)},
+    }
+    del proj_w, proj_y, wo, yo, wcat
     # ---- the other workloads, so that one run shows every level shape
     others = None
     if not args.no_other_workloads and wl.name == "C3":
@@ -420,6 +464,7 @@ def main():
         "groupnorm": groupnorm,
         "temporal_conv": temporal_conv,
         "qkv_projection": qkv_projection,
+        "temporal_layer": temporal_layer,
         "device": torch.cuda.get_device_name(0),
         "buffer_sets": n_sets,
         "roofline": roofline,

@@ -332,6 +332,44 @@ def test_projected_qkv_feed_the_attention():
     U.assert_parity(o, U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g), "bf16", what="attention")
 
 
+@pytest.mark.gpu
+def test_whole_temporal_attention_layer_stage_by_stage():
+    """The layer around the kernel, as four launches on one stream with nothing in between:
+    X -> (Q, K, V) [one launch] -> Dual-scope attention -> output projection with bias.  Every
+    stage is checked against the oracle on the bf16 tensors the previous stage produced, and the
+    end result against the oracle chain run on its own roundings."""
+    clip_len, n_clips, w, P, h, D = 16, 5, 2, 7, 8, 40
+    F, C = clip_len * n_clips, h * D
+    g = synth.stride_global_idx(F, 16).tolist()
+    print(f"[case] layer chain {n_clips}x{clip_len} frames P={P} {h}x{D} w={w} G=16", flush=True)
+    x = synth.make_tensor(F, P, C, 41, "correlated", "bf16").to(DEV)
+    ws = [synth.make_conv_weights(1, C, C, 42 + k, "bf16")[0].reshape(C, C).to(DEV) for k in range(3)]
+    wo, bo = synth.make_conv_weights(1, C, C, 46, "bf16")
+    wo, bo = wo.reshape(C, C).to(DEV), bo.to(DEV)
+    q, k, v, o, y = (torch.full_like(x, float("nan")) for _ in range(5))
+    plan = B.dsattn_plan(clip_len, n_clips, w, P, h, D, g, io_dtype=B.DSATTN_BF16, device=0)
+    assert B.dsattn_plan_launch_info(plan)["kernel"] == 1
+    B.dsattn_linear(F * P, C, C, x, ws, [q, k, v])
+    B.dsattn_forward(plan, q, k, v, o)
+    B.dsattn_linear(F * P, C, C, o, [wo], [y], biases=[bo])
+    torch.cuda.synchronize()
+    plan.close()
+    f64 = lambda t: t.to("cpu").to(torch.float64).numpy()
+    for t, wt, name in zip((q, k, v), ws, "QKV"):
+        check_conv(t, oracle.linear(f64(x), f64(wt)), "bf16", f"projection {name}")
+    U.assert_parity(o, U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g), "bf16", what="attention")
+    check_conv(y, oracle.linear(f64(o), f64(wo), bias=f64(bo)), "bf16", "output projection")
+    # the oracle chained with itself, rounding to bf16 between its stages as the tensors do
+    rb = lambda a: torch.from_numpy(a).to(torch.bfloat16).to(torch.float64).numpy()
+    qo, ko, vo = (rb(oracle.linear(f64(x), f64(wt))).reshape(F, P, h, D) for wt in ws)
+    oo = rb(oracle.forward(qo, ko, vo, clip_len, n_clips, w, g).reshape(F, P, C))
+    yo = oracle.linear(oo, f64(wo), bias=f64(bo))
+    err = np.abs(f64(y) - yo)
+    # three bf16 roundings along the way: a few bf16 ulps of the unit-scale values in between
+    assert err.max() <= 4e-2, err.max()
+    assert np.sqrt((err ** 2).mean()) <= 4e-3
+
+
 def test_conv_falls_back_when_offsets_would_not_fit_32_bits():
     # the matrix-core kernel addresses a tile's X rows and all of W with 32-bit byte offsets
     assert B.dsattn_temporal_conv_info(16, 4, 40000, 1280, 64, 16)["kernel"] == 0   # reach x P rows x c_in
