@@ -8,9 +8,8 @@ static const MfmaVariant kVariantsD128[] = {
     DSATTN_MFMA_SET(128, 1, 2),  // 1 head(s) per wavefront: rows of 128 channels
     // up to 64 global frames: four global key tiles held in registers
     DSATTN_MFMA_SET_G4(128, 1, 1),
-    // up to 128 global frames: eight global key tiles held in registers
-    // (with more than one local key tile the registers run out at this head size)
-    DSATTN_MFMA_VARIANT(128, 1, 1, 8, 1),
+    // (eight global key tiles do not fit a wavefront's registers at this head size: 65 to 128
+    // global frames run the generic kernel)
 };
 
 const MfmaVariant *mfma_variants_d128(int *n)

@@ -9,7 +9,8 @@ static const MfmaVariant kVariantsD40[] = {
     DSATTN_MFMA_SET(40, 2, 2),  // 2 head(s) per wavefront: rows of 80 channels
     DSATTN_MFMA_SET(40, 1, 2),  // 1 head(s) per wavefront: rows of 40 channels
     // up to 64 global frames: four global key tiles held in registers
-    DSATTN_MFMA_SET_G4(40, 2, 2),
+    // (two heads per wavefront with three local key tiles would spill: that shape takes one head)
+    DSATTN_MFMA_VARIANT(40, 2, 1, 4, 2), DSATTN_MFMA_VARIANT(40, 2, 2, 4, 2),
     DSATTN_MFMA_SET_G4(40, 1, 2),
     // up to 128 global frames: eight global key tiles held in registers
     DSATTN_MFMA_SET_G8(40, 2, 1),

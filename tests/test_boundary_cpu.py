@@ -423,13 +423,12 @@ def test_planning_a_very_long_video_is_quick():
 
 def test_wide_contexts_reach_the_matrix_core_kernel():
     # 16 context frames per side together with up to 64 global frames; 65 to 128 global frames
-    # where eight global key tiles fit a wavefront's registers (not at head_dim 160, and at
-    # head_dim 128 only without context frames from the neighbouring clips)
+    # where eight global key tiles fit a wavefront's registers (not at head_dim 160 and 128)
     for D, h, w, G, kernel, tiles in (
             (160, 8, 16, 64, 1, (3, 4)), (80, 8, 16, 17, 1, (3, 4)), (40, 8, 9, 64, 1, (3, 4)),
             (80, 8, 4, 128, 1, (2, 8)), (40, 8, 16, 65, 1, (3, 8)), (40, 5, 4, 128, 1, (2, 8)),
             (96, 4, 16, 128, 1, (3, 8)), (64, 4, 8, 100, 1, (2, 8)), (32, 4, 16, 128, 1, (3, 8)),
-            (128, 4, 0, 128, 1, (1, 8)), (128, 4, 2, 128, 0, None), (160, 8, 4, 65, 0, None),
+            (128, 4, 0, 128, 0, None), (128, 4, 2, 64, 1, (2, 4)), (160, 8, 4, 65, 0, None),
             (40, 5, 16, 128, 0, None), (80, 8, 4, 129, 0, None)):
         plan = B.dsattn_plan(16, 12, w, 6, h, D, [j % 192 for j in range(G)], device=-1)
         i = B.dsattn_plan_launch_info(plan)

@@ -648,7 +648,7 @@ def test_accumulator_chain_families(D, h, w, G, tiles, pairs):
     (32, 4, 16, 64, (3, 4)),
     # 65 to 128 global frames: eight global key tiles
     (80, 4, 4, 128, (2, 8)), (80, 2, 16, 100, (3, 8)), (40, 8, 4, 128, (2, 8)), (40, 3, 2, 65, (2, 8)),
-    (96, 2, 8, 128, (2, 8)), (64, 2, 16, 128, (3, 8)), (32, 4, 0, 90, (1, 8)), (128, 2, 0, 128, (1, 8)),
+    (96, 2, 8, 128, (2, 8)), (64, 2, 16, 128, (3, 8)), (32, 4, 0, 90, (1, 8)),
 ])
 def test_wide_contexts_on_matrix_cores(D, h, w, G, tiles):
     clip_len, n_clips, P = 16, 10, 3
