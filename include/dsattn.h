@@ -255,7 +255,9 @@ typedef struct dsattn_conv_info {
     int32_t tile_m;        /* output rows (frame, position) per workgroup, 0 for the generic kernel */
     int32_t tile_n;        /* output channels per workgroup */
     int32_t tile_k;        /* contraction depth per step */
-    int32_t n_blocks;      /* workgroups launched */
+    int32_t n_blocks;      /* output tiles, counted in units the 8 XCDs share evenly (the matrix-core
+                              kernel is launched with at most one persistent workgroup per compute
+                              unit, which walk them); workgroups launched for the generic kernel */
     int32_t block_threads;
     int32_t lds_bytes;
     int32_t reserved;

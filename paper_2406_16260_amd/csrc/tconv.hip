@@ -28,6 +28,7 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <type_traits>
 #include <atomic>
 
 #include "dsattn.h"
@@ -46,18 +47,9 @@ constexpr int kBK = 64;       // contraction depth per stage (bf16 elements)
 constexpr int kRow = 128;     // bytes of one LDS row: the 64 channels of a stage = one cache line
 constexpr int kSlots = 2;     // LDS ring: one stage in use, one on its way
 constexpr int kXcds = 8;
-constexpr int kLdsMax = 160 * 1024;  // LDS of a compute unit, and the cap for one workgroup
 
-// The bf16 epilogue stages a wavefront's rows in LDS, `stage_blocks` 32-row blocks at a time: as
-// many of its MI blocks as fit beside the other wavefronts' (and the bias) in the LDS.
+// One row of the bf16 epilogue's staging area: the 64-byte pieces of NJ column blocks, padded.
 __host__ __device__ constexpr int stage_row_bytes(int NJ) { return 64 * NJ + 8; }
-__host__ __device__ constexpr int stage_blocks(int MI, int NJ, int NW)
-{
-    int ib = MI;
-    while (ib > 1 && (MI % ib != 0 || NW * 32 * ib * stage_row_bytes(NJ) + NW * 32 * NJ * 4 > kLdsMax))
-        --ib;
-    return ib;
-}
 
 constexpr int kMaxGroups = 4;  // weight sets applied to the same input in one launch
 
@@ -77,9 +69,25 @@ struct ConvArgs {
     int32_t w_bytes;           // taps * c_out * c_in * 2
 };
 
+// LDS layout: ring slot 0, a gap, ring slot 1, the bias slab.  The bf16 epilogue stages every
+// wavefront's (32 rows) x (32 NJ channels) block in the slot the tile's last stage has just left
+// (the other one already holds the next tile's first stage) and may spill into the gap: from
+// slot 0 forwards, from slot 1 backwards.  The gap is what the staging area needs beyond one slot.
+__host__ __device__ constexpr int stage_gap(int BUF, int NJ, int NW)
+{
+    const int need = NW * 32 * stage_row_bytes(NJ) - BUF;
+    return need > 0 ? (need + 127) / 128 * 128 : 0;
+}
+
 // MI x NJ accumulator blocks per wavefront, WVM x WVN wavefronts per workgroup (4: one per SIMD
 // with 512 registers each; 8: two per SIMD with 256 each, which lets the hardware fill one
-// wavefront's stalls with the other's matrix instructions)
+// wavefront's stalls with the other's matrix instructions).
+//
+// The workgroups are persistent: at most one per compute unit is launched, and each walks its
+// share of the tiles.  The stages of successive tiles form one stream: while a tile's last
+// stage is multiplied out the first stage of the workgroup's next tile is already on its way
+// into the other ring slot, so only the first tile of a workgroup waits for a cold first stage,
+// and no workgroup is torn down and set up between tiles.
 template <int MI, int NJ, int WVM, int WVN, bool OUT_F32>
 __global__ __launch_bounds__(64 * WVM * WVN, WVM * WVN / 4) void tconv_mfma_kernel(const ConvArgs a)
 {
@@ -88,22 +96,29 @@ __global__ __launch_bounds__(64 * WVM * WVN, WVM * WVN / 4) void tconv_mfma_kern
     constexpr int GA = BM / 8 / NW, GB = BN / 8 / NW;  // 8-row groups (one load instruction) per wavefront
     static_assert(GA * 8 * NW == BM && GB * 8 * NW == BN, "the wavefronts share the loads evenly");
     constexpr int ABYTES = BM * kRow, BUF = (BM + BN) * kRow;  // one ring slot
+    constexpr int SLOT = BUF + stage_gap(BUF, NJ, NW);         // distance between the two slots
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
-    // workgroup -> tile: XCD x (= blockIdx % 8) walks tiles [x * per_xcd, (x + 1) * per_xcd)
-    const int tile = (int)(blockIdx.x % kXcds) * a.per_xcd + (int)(blockIdx.x / kXcds);
-    if (tile >= a.tiles) return;  // whole workgroup: no barrier has been reached yet
-    // group outermost, then row tile, column tile fastest: the 32 tiles in flight on an XCD are
-    // all column tiles of a few neighbouring row tiles of one group, about as many X slabs as W
-    // slabs (with the groups side by side they would be 2 row tiles against 3 x 5 column tiles
-    // and fetch W three times as often: measured 15 GB instead of 6 GB from HBM)
+    // workgroup -> tiles: XCD x (= blockIdx % 8) owns tiles [x * per_xcd, (x + 1) * per_xcd); its
+    // gridDim / 8 workgroups take them in turn, so the tiles in flight on an XCD at any time are
+    // neighbours.  Tiles are numbered group outermost, then row tile, column tile fastest: the
+    // tiles in flight on an XCD are all column tiles of a few neighbouring row tiles of one
+    // group, about as many X slabs as W slabs (with the groups side by side they would be 2 row
+    // tiles against 3 x 5 column tiles and fetch W three times as often: measured 15 GB instead
+    // of 6 GB from HBM).
+    const int xcd = (int)(blockIdx.x % kXcds);
+    const int nper = (int)(gridDim.x / kXcds);  // workgroups per XCD
+    const int t_end = min((xcd + 1) * a.per_xcd, a.tiles);
+    int tile_c = xcd * a.per_xcd + (int)(blockIdx.x / kXcds);  // the tile being multiplied out
+    if (tile_c >= t_end) return;  // whole workgroup: no barrier has been reached yet
     const int tiles_grp = a.tiles_m * a.tiles_n;
-    const int grp = tile / tiles_grp, rem = tile - grp * tiles_grp;
-    const int mt = rem / a.tiles_n, nt = rem - mt * a.tiles_n;
-    const int64_t m0 = (int64_t)mt * BM;
-    const int n0 = nt * BN;
-    const float *gbias = a.bias[grp];
-    void *gY = a.Y[grp];
+    auto decode = [&](int tile, int &grp, int64_t &m0, int &n0) __attribute__((always_inline)) {
+        grp = tile / tiles_grp;
+        const int rem = tile - grp * tiles_grp;
+        const int mt = rem / a.tiles_n, nt = rem - mt * a.tiles_n;
+        m0 = (int64_t)mt * BM;
+        n0 = nt * BN;
+    };
 
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -123,12 +138,6 @@ __global__ __launch_bounds__(64 * WVM * WVN, WVM * WVN / 4) void tconv_mfma_kern
     // multiply into belongs to output channels that are never stored.
     const int lr = lane >> 3;
     const int lc = (lane & 7) ^ lr;
-    const int64_t rb = max((int64_t)0, m0 - (int64_t)a.n * a.P);  // first row the tile can touch
-    const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)((const __bf16 *)a.X + rb * a.Cin), 0,
-        (int)min((a.M - rb) * a.Cin * 2, (int64_t)0x7fffffff), 0x00020000);
-    const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)a.W[grp], 0, (int)a.w_bytes, 0x00020000);
     const int rowbytes = a.Cin * 2;
     constexpr uint32_t kOob = 0xfffffff0u;
     int xoff[GA], woff[GB];  // byte offset of this lane's row and chunk within the tile's rows
@@ -145,32 +154,55 @@ __global__ __launch_bounds__(64 * WVM * WVN, WVM * WVN / 4) void tconv_mfma_kern
         asm volatile("" : "+v"(woff[l]));
     }
 
-    // per-stage load state, set by stage_setup(), used by issue_one()
+    // ---- the load side: the tile whose stages are being fetched (it runs ahead of the tile being
+    // multiplied out by up to two stages), its descriptors, and the per-stage load state
+    int ld_tile = tile_c - nper;  // ld_open() advances before use
+    bool ld_has = false;          // there is such a tile
+    int ld_n0 = 0;
+    int64_t ld_m0 = 0, ld_rb = 0;
+    __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc((void *)a.X, 0, 0, 0x00020000);
+    __amdgpu_buffer_rsrc_t wres = xres;
+    const int taps = 2 * a.n + 1;
+    int su_kc = 0, su_t = 0, su_ks = a.KS;  // channel block, tap and stage number within the load tile
+    int ld_gs = 0;                          // stages set up so far: the ring slot is ld_gs % 2
+    auto ld_open = [&]() __attribute__((always_inline)) {
+        ld_tile += nper;
+        ld_has = ld_tile < t_end;
+        int grp = 0;
+        decode(ld_has ? ld_tile : tile_c, grp, ld_m0, ld_n0);
+        ld_rb = max((int64_t)0, ld_m0 - (int64_t)a.n * a.P);  // first row the tile can touch
+        xres = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)((const __bf16 *)a.X + ld_rb * a.Cin), 0,
+            (int)min((a.M - ld_rb) * a.Cin * 2, (int64_t)0x7fffffff), 0x00020000);
+        wres = __builtin_amdgcn_make_buffer_rsrc((void *)a.W[grp], 0, (int)a.w_bytes, 0x00020000);
+        su_kc = su_t = su_ks = 0;
+    };
     uint32_t ld_xstep = 0, ld_wstep = 0;
     bool ld_live = false;  // this lane's channels exist (and the stage does)
     unsigned char *ld_as = smem, *ld_bs = smem;
-    // stage ks = channel block * taps + tap: the taps of one channel block follow each other,
-    // so that the X lines they share (the same rows, shifted by P per tap) are still in L2.
-    // Past the last stage every lane of the loads is an out-of-range one: no traffic, the same
-    // number of loads in flight, and no branch inside the multiply schedule.
-    // The calls come with ks = 0, 1, 2, ... in order, so the channel block and the tap are
-    // counted along instead of being divided out of ks (a scalar division is some forty
-    // instructions, and they would sit between two matrix instructions).
-    const int taps = 2 * a.n + 1;
-    int su_kc = 0, su_t = 0;
-    auto stage_setup = [&](int ks) __attribute__((always_inline)) {
+    // Sets up the next stage of the stream.  Stage number within a tile = channel block * taps +
+    // tap: the taps of one channel block follow each other, so that the X lines they share (the
+    // same rows, shifted by P per tap) are still in L2; both are counted along instead of being
+    // divided out (a scalar division is some forty instructions, and they would sit between two
+    // matrix instructions).  Past the workgroup's last tile every lane of the loads is an
+    // out-of-range one: no traffic, the same number of loads in flight, and no branch inside the
+    // multiply schedule.
+    auto stage_setup = [&]() __attribute__((always_inline)) {
+        if (su_ks == a.KS) ld_open();
         const int kc = su_kc, t = su_t;
+        ++su_ks;
         if (++su_t == taps) {
             su_t = 0;
             ++su_kc;
         }
-        ld_live = ks < a.KS && kc * kBK + lc * 8 < a.Cin;  // c_in % 8 == 0: a chunk is all in or out
-        const int64_t mshift = m0 + (int64_t)(t - a.n) * a.P;  // video row of tile row 0 at this tap
-        ld_xstep = (uint32_t)((int)(mshift - rb) * rowbytes + kc * (kBK * 2));
-        ld_wstep = (uint32_t)((t * a.Cout + n0) * rowbytes + kc * (kBK * 2));
-        const int slot = ks & (kSlots - 1);
-        ld_as = smem + slot * BUF + wv * (GA * 1024);
-        ld_bs = smem + slot * BUF + ABYTES + wv * (GB * 1024);
+        ld_live = ld_has && kc * kBK + lc * 8 < a.Cin;  // c_in % 8 == 0: a chunk is all in or out
+        const int64_t mshift = ld_m0 + (int64_t)(t - a.n) * a.P;  // video row of tile row 0 at this tap
+        ld_xstep = (uint32_t)((int)(mshift - ld_rb) * rowbytes + kc * (kBK * 2));
+        ld_wstep = (uint32_t)((t * a.Cout + ld_n0) * rowbytes + kc * (kBK * 2));
+        const int slot = ld_gs & (kSlots - 1);
+        ++ld_gs;
+        ld_as = smem + slot * SLOT + wv * (GA * 1024);
+        ld_bs = smem + slot * SLOT + ABYTES + wv * (GB * 1024);
     };
     constexpr int NL = GA + GB;  // loads per wavefront and stage
     auto issue_one = [&](int l) __attribute__((always_inline)) {
@@ -187,12 +219,15 @@ __global__ __launch_bounds__(64 * WVM * WVN, WVM * WVN / 4) void tconv_mfma_kern
     // acc[i][j] is the 32 x 32 block (32 output channels) x (32 rows of Y): W rows are the A
     // operand, X rows the B operand, so that a lane ends up with 4 consecutive channels of one row
     f32x16 acc[MI][NJ];
+    auto clear_acc = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < NJ; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    };
+    clear_acc();
 
     // operand addresses: MFMA row/column lane & 31 (row % 8 = lane % 8), contraction group
     // lane >> 5; sub-step kk needs chunk 2 kk + (lane >> 5), which sits at position chunk ^ (row % 8)
@@ -228,15 +263,16 @@ __global__ __launch_bounds__(64 * WVM * WVN, WVM * WVN / 4) void tconv_mfma_kern
     // multiplies [mlo, mhi) of the sub-step whose fragments are in `slot`; read r of the next
     // fragments (sub-step kk of `base`) goes before multiply mlo + floor(r (mhi - mlo) / NR)
     // when do_reads; g0 is the number of multiplies since the barrier at multiply mlo: load q
-    // goes before the multiply that is number floor(q kSpread / NL) since the barrier
+    // goes before the multiply that is number floor(q kSpread / NL) since the barrier (when
+    // do_loads)
     auto mma_range = [&](int slot, int mlo, int mhi, bool do_reads, const unsigned char *base, int kk,
-                         int g0) __attribute__((always_inline)) {
+                         int g0, bool do_loads) __attribute__((always_inline)) {
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
             if (m < mlo || m >= mhi) continue;
 #pragma unroll
             for (int q = 0; q < NL; ++q)
-                if ((q * kSpread) / NL == g0 + m - mlo) {
+                if (do_loads && (q * kSpread) / NL == g0 + m - mlo) {
                     issue_one(q);
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -252,151 +288,199 @@ __global__ __launch_bounds__(64 * WVM * WVN, WVM * WVN / 4) void tconv_mfma_kern
             __builtin_amdgcn_sched_barrier(0);
         }
     };
+    // the loads of the stage just set up that go before the first multiplies after a barrier
+    auto issue_tail_loads = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < NL; ++q)
+            if ((q * kSpread) / NL < TAIL) issue_one(q);
+    };
 
-    // prologue: stage 0 landed, the first loads of stage 1 issued as the loop's tail would have.
-    // (Bare barriers: the wait before them is the only ordering needed.)
-    stage_setup(0);
+    // LDS behind the two ring slots: the bias of each wavefront's 32 NJ channels
+    constexpr int kBiasOff = SLOT + BUF;
+    float *bl = (float *)(smem + kBiasOff) + wv * (32 * NJ);
+    constexpr int NBR = (32 * NJ + 63) / 64;  // bias values a lane carries from a tile's start to its end
+
+    // ---- start of the stream: the first tile's first stage landed, the first loads of its
+    // second stage issued as the loop's tail would have.  (Bare barriers: the wait before them is
+    // the only ordering needed.)
+    stage_setup();
 #pragma unroll
     for (int l = 0; l < NL; ++l) issue_one(l);
-    {
-        // the bias of this wavefront's 32 NJ channels goes into LDS now (zeros where there is
-        // no bias or no channel), behind everything the loop touches: the stores of the
-        // epilogue then depend on no global load
-        constexpr int kStageBytes = NW * 32 * stage_blocks(MI, NJ, NW) * stage_row_bytes(NJ);
-        constexpr int kBiasOff = (kSlots * BUF > kStageBytes) ? kSlots * BUF : kStageBytes;
-        float *bw = (float *)(smem + kBiasOff) + wv * (32 * NJ);
-        const int cb = n0 + wn * 32 * NJ;
-#pragma unroll
-        for (int c = lane; c < 32 * NJ; c += 64)
-            bw[c] = (gbias && cb + c < a.Cout) ? gbias[cb + c] : 0.f;
-    }
     __builtin_amdgcn_s_waitcnt(0);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    stage_setup(1);
-#pragma unroll
-    for (int q = 0; q < NL; ++q)
-        if ((q * kSpread) / NL < TAIL) issue_one(q);
+    stage_setup();
+    issue_tail_loads();
 #pragma unroll
     for (int r = 0; r < NR; ++r) read_frag(smem, 0, 0, r);
 
-    for (int ks = 0; ks < a.KS; ++ks) {
-        const unsigned char *bufc = smem + (ks & 1) * BUF;
-        const unsigned char *bufn = smem + ((ks + 1) & 1) * BUF;
+    int cs = 0;  // stages multiplied out so far: the current ring slot is cs % 2
+    for (;;) {
+        int grp;
+        int64_t m0;
+        int n0;
+        decode(tile_c, grp, m0, n0);
+        const float *gbias = a.bias[grp];
+        void *gY = a.Y[grp];
+        const int cbase = n0 + wn * 32 * NJ;      // first channel of this wavefront's part
+        const int64_t mrow0 = m0 + wm * 32 * MI;  // first row of this wavefront's part
+        // the bias of this wavefront's channels is fetched now and put into LDS before the
+        // epilogue: the stores of the epilogue then wait for no global load
+        float breg[NBR];
 #pragma unroll
-        for (int kk = 0; kk + 1 < NKK; ++kk)
-            mma_range(kk & 1, 0, NM, true, bufc, kk + 1, TAIL + kk * NM);
-        // last sub-step: half of its multiplies, then the barrier (this wavefront's loads of
-        // stage ks + 1 have landed; after the barrier everybody's have, and every wavefront
-        // has left slot ks % 2), then the first fragments of the next stage and the first
-        // loads of the stage after it interleaved with the other half.  After the last stage
-        // those fragments are never used: the reads stay in bounds, and keeping them
-        // unconditional keeps the multiplies out of divergent control flow.
-        // (the addresses of the stage after next are worked out before the barrier, under the
-        // multiplies: every load of stage ks + 1 has been issued by now, see kSpread)
-        stage_setup(ks + 2);
-        mma_range((NKK - 1) & 1, 0, NM / 2, false, bufc, 0, TAIL + (NKK - 1) * NM);
-        __builtin_amdgcn_s_waitcnt(0);
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-        mma_range((NKK - 1) & 1, NM / 2, NM, true, bufn, 0, 0);
-    }
-    // the loop's last barrier has retired every load (the last stage's were the out-of-range
-    // ones of the stage past the end, which write zeros) and every operand read that matters
+        for (int u = 0; u < NBR; ++u) {
+            const int c = lane + 64 * u;
+            breg[u] = (gbias && c < 32 * NJ && cbase + c < a.Cout) ? gbias[cbase + c] : 0.f;
+        }
 
-    // epilogue: accumulator element e of lane l is output channel 8 (e / 4) + 4 (l / 32) + e % 4
-    // and row l % 32 of its block: four consecutive channels per lane and e / 4.
-    constexpr int SROW = stage_row_bytes(NJ);
-    constexpr int IB = stage_blocks(MI, NJ, NW);
-    constexpr int STAGE = 32 * IB * SROW;
-    constexpr int BIAS_OFF = (kSlots * BUF > NW * STAGE) ? kSlots * BUF : NW * STAGE;
-    const int cbase = n0 + wn * 32 * NJ;     // first channel of this wavefront's part
-    const int64_t mrow0 = m0 + wm * 32 * MI;  // first row of this wavefront's part
-    const float *bl = (const float *)(smem + BIAS_OFF) + wv * (32 * NJ);  // written in the prologue
+        for (int ks = 0; ks < a.KS; ++ks, ++cs) {
+            const unsigned char *bufc = smem + (cs & 1) * SLOT;
+            const unsigned char *bufn = smem + ((cs + 1) & 1) * SLOT;
+#pragma unroll
+            for (int kk = 0; kk + 1 < NKK; ++kk)
+                mma_range(kk & 1, 0, NM, true, bufc, kk + 1, TAIL + kk * NM, true);
+            // last sub-step: half of its multiplies, then the barrier (this wavefront's loads of
+            // the next stage have landed; after the barrier everybody's have, and every
+            // wavefront has left the current slot), then the first fragments of the next stage
+            // and the first loads of the stage after it interleaved with the other half.  The
+            // addresses of the stage after next are worked out before the barrier, under the
+            // multiplies: every load of the next stage has been issued by now (see kSpread).
+            // After the workgroup's last stage those fragments are never used: the reads stay in
+            // bounds, and keeping them unconditional keeps the multiplies out of divergent
+            // control flow.
+            stage_setup();
+            mma_range((NKK - 1) & 1, 0, NM / 2, false, bufc, 0, TAIL + (NKK - 1) * NM, true);
+            __builtin_amdgcn_s_waitcnt(0);
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            // After a tile's last stage the slot just left is the epilogue's staging area, so the
+            // loads that would go into it wait until the epilogue is through (a scalar branch
+            // around each of these few loads; two copies of the multiplies, one with and one
+            // without them, made the compiler spill accumulators).
+            mma_range((NKK - 1) & 1, NM / 2, NM, true, bufn, 0, 0, ks + 1 < a.KS);
+        }
+        // The tile's last barrier has retired every load into, and every operand read of, the slot
+        // of its last stage, (cs - 1) % 2; the other slot holds the next tile's first stage.
 
-    if constexpr (!OUT_F32) {
-        if ((a.Cout & 7) == 0) {
-            // bf16 rows made of whole 16-byte pieces: the wavefront's (32 MI) x (32 NJ) part goes
-            // through its own LDS region, IB 32-row blocks at a time (the loop's last barrier
-            // has retired every load and every read of the operand buffers that matters), and
-            // leaves as full rows: each store instruction writes 64 NJ contiguous bytes per
-            // row.  Rows are padded by 8 bytes so that the 8-byte writes of 32 consecutive rows
-            // spread over the banks.
-            constexpr int CPR = 4 * NJ;  // 16-byte pieces per row
-            unsigned char *stg = smem + wv * STAGE;
+        // ---- epilogue: accumulator element e of lane l is output channel 8 (e / 4) + 4 (l / 32) +
+        // e % 4 and row l % 32 of its block: four consecutive channels per lane and e / 4.
+        // (the lane index is made opaque once per tile: every address below depends on it, and
+        // what the compiler could otherwise compute ahead of the tile loop and keep alive through
+        // it costs the main loop its registers)
+        int le = lane;
+        asm volatile("" : "+v"(le));
 #pragma unroll
-            for (int i0 = 0; i0 < MI; i0 += IB) {
+        for (int u = 0; u < NBR; ++u)
+            if (le + 64 * u < 32 * NJ) bl[le + 64 * u] = breg[u];
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        bool staged = false;
+        if constexpr (!OUT_F32) {
+            if ((a.Cout & 7) == 0) {
+                staged = true;
+                // bf16 rows made of whole 16-byte pieces: the wavefront's (32 MI) x (32 NJ) part
+                // goes through its own region of the staging area, one 32-row block at a time, and
+                // leaves as full rows: each store instruction writes 64 NJ contiguous bytes per
+                // row.  Rows are padded by 8 bytes so that the 8-byte writes of 32 consecutive rows
+                // spread over the banks.
+                constexpr int SR = stage_row_bytes(NJ);
+                constexpr int CPR = 4 * NJ;  // 16-byte pieces per row
+                unsigned char *stg = smem + (((cs - 1) & 1) ? SLOT + BUF - NW * 32 * SR : 0) + wv * (32 * SR);
 #pragma unroll
-                for (int j = 0; j < NJ; ++j)
+                for (int i = 0; i < MI; ++i) {
+                    // (without a bias the additions are left out: they are a third of this phase's
+                    // vector instructions, and the phase is bound by them)
+                    auto fill = [&](auto with_bias) __attribute__((always_inline)) {
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int cl = 32 * j + 8 * g + 4 * (lane >> 5);  // channel within the part
-                        const f32x4 b = *(const f32x4 *)(bl + cl);
+                        for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                        for (int ii = 0; ii < IB; ++ii) {
-                            bf16x4 yb;
+                            for (int g = 0; g < 4; ++g) {
+                                const int cl = 32 * j + 8 * g + 4 * (le >> 5);  // channel within the part
+                                f32x4 b = {0.f, 0.f, 0.f, 0.f};
+                                if constexpr (decltype(with_bias)::value) b = *(const f32x4 *)(bl + cl);
+                                bf16x4 yb;
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) {
+                                    float y = acc[i][j][4 * g + e];
+                                    if constexpr (decltype(with_bias)::value) y += b[e];
+                                    yb[e] = (__bf16)y;
+                                }
+                                *(bf16x4 *)(stg + (le & 31) * SR + cl * 2) = yb;
+                            }
+                    };
+                    if (gbias)
+                        fill(std::true_type{});
+                    else
+                        fill(std::false_type{});
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int it = 0; it < (32 * CPR + 63) / 64; ++it) {
+                        const int q = le + 64 * it;
+                        const int row = q / CPR, pc = q - row * CPR;
+                        const int64_t m = mrow0 + 32 * i + row;
+                        if (q < 32 * CPR && m < a.M && cbase + pc * 8 < a.Cout) {
+                            const uint2 lo = *(const uint2 *)(stg + row * SR + pc * 16);
+                            const uint2 hi = *(const uint2 *)(stg + row * SR + pc * 16 + 8);
+                            *(uint4 *)((__bf16 *)gY + m * a.Cout + cbase + pc * 8) =
+                                make_uint4(lo.x, lo.y, hi.x, hi.y);
+                        }
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                }
+            }
+        }
+        if (!staged) {
+            // fp32 output, or bf16 rows that are not whole 16-byte pieces: straight from the registers
+            const bool vec_ok = (a.Cout & 3) == 0;  // 8-byte (bf16) / 16-byte (fp32) stores stay aligned
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int cl = 32 * j + 8 * g + 4 * (le >> 5);
+                    const int co = cbase + cl;
+                    const f32x4 b = *(const f32x4 *)(bl + cl);
+#pragma unroll
+                    for (int i = 0; i < MI; ++i) {
+                        const int64_t m = mrow0 + 32 * i + (le & 31);
+                        if (m >= a.M || co >= a.Cout) continue;
+                        const f32x4 y = {acc[i][j][4 * g] + b[0], acc[i][j][4 * g + 1] + b[1],
+                                         acc[i][j][4 * g + 2] + b[2], acc[i][j][4 * g + 3] + b[3]};
+                        if (vec_ok) {  // c_out % 4 == 0 and co % 4 == 0: all four channels exist
+                            if constexpr (OUT_F32) {
+                                *(f32x4 *)((float *)gY + m * a.Cout + co) = y;
+                            } else {
+                                bf16x4 yb;
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) yb[e] = (__bf16)y[e];
+                                *(bf16x4 *)((__bf16 *)gY + m * a.Cout + co) = yb;
+                            }
+                        } else {
 #pragma unroll
                             for (int e = 0; e < 4; ++e)
-                                yb[e] = (__bf16)(acc[i0 + ii][j][4 * g + e] + b[e]);
-                            *(bf16x4 *)(stg + (32 * ii + (lane & 31)) * SROW + cl * 2) = yb;
+                                if (co + e < a.Cout) {
+                                    if constexpr (OUT_F32)
+                                        ((float *)gY)[m * a.Cout + co + e] = y[e];
+                                    else
+                                        ((__bf16 *)gY)[m * a.Cout + co + e] = (__bf16)y[e];
+                                }
                         }
                     }
-                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-#pragma unroll
-                for (int it = 0; it < (32 * IB * CPR + 63) / 64; ++it) {
-                    const int q = lane + 64 * it;
-                    const int row = q / CPR, pc = q - row * CPR;
-                    const int64_t m = mrow0 + 32 * i0 + row;
-                    if (q < 32 * IB * CPR && m < a.M && cbase + pc * 8 < a.Cout) {
-                        const uint2 lo = *(const uint2 *)(stg + row * SROW + pc * 16);
-                        const uint2 hi = *(const uint2 *)(stg + row * SROW + pc * 16 + 8);
-                        *(uint4 *)((__bf16 *)gY + m * a.Cout + cbase + pc * 8) =
-                            make_uint4(lo.x, lo.y, hi.x, hi.y);
-                    }
                 }
-                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-            }
-            return;
         }
+
+        // ---- on to the workgroup's next tile: its first stage is in the other slot and its first
+        // fragments are in registers; the loads held back above go out once every wavefront has
+        // left the staging area
+        tile_c += nper;
+        if (tile_c >= t_end) break;
+        clear_acc();
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        issue_tail_loads();
     }
-    // fp32 output, or bf16 rows that are not whole 16-byte pieces: straight from the registers
-    const bool vec_ok = (a.Cout & 3) == 0;  // 8-byte (bf16) / 16-byte (fp32) stores stay aligned
-#pragma unroll
-    for (int j = 0; j < NJ; ++j)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int cl = 32 * j + 8 * g + 4 * (lane >> 5);
-            const int co = cbase + cl;
-            const f32x4 b = *(const f32x4 *)(bl + cl);
-#pragma unroll
-            for (int i = 0; i < MI; ++i) {
-                const int64_t m = mrow0 + 32 * i + (lane & 31);
-                if (m >= a.M || co >= a.Cout) continue;
-                const f32x4 y = {acc[i][j][4 * g] + b[0], acc[i][j][4 * g + 1] + b[1],
-                                 acc[i][j][4 * g + 2] + b[2], acc[i][j][4 * g + 3] + b[3]};
-                if (vec_ok) {  // c_out % 4 == 0 and co % 4 == 0: all four channels exist
-                    if constexpr (OUT_F32) {
-                        *(f32x4 *)((float *)gY + m * a.Cout + co) = y;
-                    } else {
-                        bf16x4 yb;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) yb[e] = (__bf16)y[e];
-                        *(bf16x4 *)((__bf16 *)gY + m * a.Cout + co) = yb;
-                    }
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (co + e < a.Cout) {
-                            if constexpr (OUT_F32)
-                                ((float *)gY)[m * a.Cout + co + e] = y[e];
-                            else
-                                ((__bf16 *)gY)[m * a.Cout + co + e] = (__bf16)y[e];
-                        }
-                }
-            }
-        }
 }
 
 // Plain vector kernel for every other case (fp32 tensors, c_in not a multiple of 8): one
@@ -471,8 +555,9 @@ const ConvVariant *conv_pick(const dsattn_conv_desc &d, int64_t M, int groups = 
     if (taps * d.c_out * d.c_in * 2 >= ((int64_t)1 << 31)) return nullptr;
     if ((320 + 2 * (int64_t)d.reach * d.spatial) * d.c_in * 2 >= ((int64_t)1 << 31)) return nullptr;
     // least multiplied-out area (padding of the last row and column tiles), then the larger
-    // tile (fewer prologues and epilogues), then four wavefronts (measured a little faster than
-    // eight at equal tile size); DSATTN_CONV_WAVES=4|8 restricts the choice for A/B runs
+    // tile (fewer epilogues), then eight wavefronts (the four-wavefront variants hold a whole
+    // 256-register accumulator per lane and spill two to four registers around the tile change);
+    // DSATTN_CONV_WAVES=4|8 restricts the choice for A/B runs
     int want_waves = 0;
     if (const char *e = getenv("DSATTN_CONV_WAVES")) {
         const int w = atoi(e);
@@ -490,7 +575,7 @@ const ConvVariant *conv_pick(const dsattn_conv_desc &d, int64_t M, int groups = 
         const int64_t tiles = tm * tn;
         const bool better = !best || area < best_area ||
                             (area == best_area && (tiles < best_tiles ||
-                                                   (tiles == best_tiles && v.waves() < best->waves())));
+                                                   (tiles == best_tiles && v.waves() > best->waves())));
         if (better) {
             best = &v;
             best_area = area;
@@ -500,13 +585,27 @@ const ConvVariant *conv_pick(const dsattn_conv_desc &d, int64_t M, int groups = 
     return best;
 }
 
-// the ring of operand slots, reused by the bf16 epilogue as four (32 MI) x (64 NJ + 8)-byte
-// regions; behind them the bias of each wavefront's 32 NJ channels
+// the two ring slots with the staging gap between them; behind them the bias of each
+// wavefront's 32 NJ channels
 int conv_lds_bytes(const ConvVariant &v)
 {
-    return std::max(kSlots * (v.bm() + v.bn()) * kRow,
-                    v.waves() * 32 * stage_blocks(v.MI, v.NJ, v.waves()) * stage_row_bytes(v.NJ)) +
-           v.waves() * 32 * v.NJ * (int)sizeof(float);
+    const int buf = (v.bm() + v.bn()) * kRow;
+    return kSlots * buf + stage_gap(buf, v.NJ, v.waves()) + v.waves() * 32 * v.NJ * (int)sizeof(float);
+}
+
+// Compute units of the current device (one persistent workgroup is launched per unit at most).
+int conv_compute_units(int dev)
+{
+    static std::atomic<int> cached[64];
+    if (dev >= 0 && dev < 64) {
+        const int c = cached[dev].load(std::memory_order_relaxed);
+        if (c > 0) return c;
+    }
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+        n = 256;
+    if (dev >= 0 && dev < 64) cached[dev].store(n, std::memory_order_relaxed);
+    return n;
 }
 
 // A linear layer over M rows is the one-tap case of the convolution (every row its own frame).
@@ -577,7 +676,9 @@ hipError_t conv_launch(const dsattn_conv_desc &d, int64_t M, const ConvVariant *
         a.per_xcd = (a.tiles + kXcds - 1) / kXcds;
         a.w_bytes = (int32_t)((2 * (int64_t)d.reach + 1) * d.c_out * d.c_in * 2);
         void *params[] = {&a};
-        return hipLaunchKernel(fn, dim3((unsigned)(a.per_xcd * kXcds)), dim3(64 * v->waves()), params,
+        // persistent workgroups: one per compute unit at most, the same number on every XCD
+        const int per_xcd_wg = std::min(a.per_xcd, (conv_compute_units(dev) + kXcds - 1) / kXcds);
+        return hipLaunchKernel(fn, dim3((unsigned)(per_xcd_wg * kXcds)), dim3(64 * v->waves()), params,
                                (size_t)lds, st);
     }
     const int64_t total = M * d.c_out;
