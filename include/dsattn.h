@@ -313,6 +313,35 @@ int dsattn_linear_info(const dsattn_linear_desc *desc, dsattn_conv_info *info);
 int dsattn_linear(const dsattn_linear_desc *desc, const void *X, const void *const *W,
                   const float *const *bias, void *const *Y, void *stream);
 
+/*
+ * One whole temporal-attention layer on the caller's stream (Section 4.2, "Attention module":
+ * queries, keys and values are computed from the tokens, each clip attends to its local and
+ * global context, and the result is projected back):
+ *   Q, K, V = X Wq^T + bq, X Wk^T + bk, X Wv^T + bv     one launch, X read once
+ *   A       = Dual-scope attention(Q, K, V)              dsattn_forward of `plan`
+ *   Y       = A Wo^T + bo                                one launch
+ * Three kernels enqueued back to back with no host work and no allocation in between; the
+ * intermediate tensors live in the caller's workspace (Q, K, V, A in that order, each [F, P, C]
+ * of io_dtype at a 256-byte aligned offset).  The three stages are not merged into one kernel:
+ * a workgroup of the projection needs all C channels of 256 tokens, a workgroup of the attention
+ * all frames of one position.
+ *   plan      : for a device; out_dtype must equal io_dtype (EUNSUPPORTED otherwise)
+ *   X         : device, [F, P, C] of io_dtype, C = heads * head_dim, 16-byte aligned
+ *   W         : HOST array of 4 device pointers Wq, Wk, Wv, Wo, each [C][C] of io_dtype
+ *               (output channel major, as for dsattn_linear), 16-byte aligned
+ *   bias      : NULL, or HOST array of 4 device pointers (entries may be NULL), each [C] fp32
+ *   workspace : device, at least dsattn_temporal_layer_workspace() bytes, 256-byte aligned,
+ *               overlapping neither X nor Y; contents on return: Q, K, V, A
+ *   Y         : device, [F, P, C] of io_dtype; may be X itself (X is consumed by the first
+ *               stage), must not overlap it otherwise
+ * Errors: those of dsattn_linear and dsattn_forward; EINVAL for a short or misaligned workspace.
+ * After a failure in a later stage the earlier stages stay enqueued.
+ */
+int dsattn_temporal_layer_workspace(const dsattn_plan_t *plan, size_t *bytes);
+int dsattn_temporal_layer(const dsattn_plan_t *plan, const void *X, const void *const *W,
+                          const float *const *bias, void *workspace, size_t workspace_bytes,
+                          void *Y, void *stream);
+
 /* Static description of a status code; never NULL. */
 const char *dsattn_strerror(int code);
 

@@ -32,6 +32,7 @@ EXPORTS = (
     "dsattn_copy_probe", "dsattn_strerror", "dsattn_last_error", "dsattn_groupnorm_workspace",
     "dsattn_groupnorm", "dsattn_temporal_conv_info", "dsattn_temporal_conv", "dsattn_linear_info",
     "dsattn_linear", "dsattn_groupnorm_static", "dsattn_groupnorm_static_max_bytes",
+    "dsattn_temporal_layer_workspace", "dsattn_temporal_layer",
 )
 
 
@@ -158,6 +159,11 @@ def load():
     lib.dsattn_groupnorm_static.argtypes = [ctypes.POINTER(DsattnGnDesc), vp, vp, vp, vp, vp, vp]
     lib.dsattn_groupnorm_static_max_bytes.restype = ctypes.c_size_t
     lib.dsattn_groupnorm_static_max_bytes.argtypes = []
+    lib.dsattn_temporal_layer_workspace.restype = ctypes.c_int
+    lib.dsattn_temporal_layer_workspace.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.dsattn_temporal_layer.restype = ctypes.c_int
+    lib.dsattn_temporal_layer.argtypes = [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp,
+                                          ctypes.c_size_t, vp, vp]
     lib.dsattn_strerror.restype = ctypes.c_char_p
     lib.dsattn_strerror.argtypes = [ctypes.c_int]
     lib.dsattn_last_error.restype = ctypes.c_char_p
@@ -464,3 +470,35 @@ def dsattn_linear(rows, c_in, c_out, X, Ws, Ys, biases=None, io_dtype=DSATTN_BF1
     _check(load().dsattn_linear(ctypes.byref(desc), _ptr(X), _ptr_array(Ws, n),
                                 None if biases is None else _ptr_array(biases, n),
                                 _ptr_array(Ys, n), _stream(stream)), "dsattn_linear")
+
+
+def dsattn_temporal_layer_workspace(plan):
+    """Bytes of device workspace dsattn_temporal_layer needs for this plan."""
+    n = ctypes.c_size_t(0)
+    _check(load().dsattn_temporal_layer_workspace(plan.handle, ctypes.byref(n)),
+           "dsattn_temporal_layer_workspace")
+    return int(n.value)
+
+
+def dsattn_temporal_layer(plan, X, Ws, workspace, Y, biases=None, stream=None):
+    """Ws = (Wq, Wk, Wv, Wo), biases = None or four entries (each a tensor or None); workspace: a
+    uint8 device tensor of at least dsattn_temporal_layer_workspace(plan) bytes."""
+    if len(Ws) != 4 or (biases is not None and len(biases) != 4):
+        raise ValueError("dsattn_temporal_layer: four weight sets (and four bias entries) expected")
+    C = plan.C
+    items = [plan.frames(X, "X"), plan.frames(Y, "Y")]
+    for g in range(4):
+        items.append((Ws[g], f"W[{g}]", C * C, plan.desc.io_dtype))
+        if biases is not None:
+            items.append((biases[g], f"bias[{g}]", C, DSATTN_F32))
+    nbytes = 0
+    if hasattr(workspace, "data_ptr"):
+        if workspace.element_size() != 1:
+            raise ValueError("dsattn_temporal_layer: workspace: a byte tensor (uint8) expected")
+        nbytes = workspace.numel()
+        items.append((workspace, "workspace", ("min", 0), None))
+    plan.check("dsattn_temporal_layer", items)
+    _check(load().dsattn_temporal_layer(plan.handle, _ptr(X), _ptr_array(Ws, 4),
+                                        None if biases is None else _ptr_array(biases, 4),
+                                        _ptr(workspace), nbytes, _ptr(Y), _stream(stream)),
+           "dsattn_temporal_layer")

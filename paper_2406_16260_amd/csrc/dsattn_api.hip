@@ -306,6 +306,64 @@ int dsattn_forward_ctx(const dsattn_plan_t *plan, const void *Q, const void *Kct
     return DSATTN_OK;
 }
 
+// One [F, P, C] tensor of the layer's workspace, rounded up so that the next one stays aligned.
+static size_t layer_slab_bytes(const dsattn_plan_t &pl)
+{
+    const size_t n = (size_t)pl.F * pl.desc.spatial * pl.C * dtype_size(pl.desc.io_dtype);
+    return (n + 255) / 256 * 256;
+}
+
+int dsattn_temporal_layer_workspace(const dsattn_plan_t *plan, size_t *bytes)
+{
+    if (!plan || !bytes) return fail(DSATTN_EINVAL, "dsattn_temporal_layer_workspace: null argument");
+    *bytes = 4 * layer_slab_bytes(*plan);
+    return DSATTN_OK;
+}
+
+int dsattn_temporal_layer(const dsattn_plan_t *plan, const void *X, const void *const *W,
+                          const float *const *bias, void *workspace, size_t workspace_bytes, void *Y,
+                          void *stream)
+{
+    const char *who = "dsattn_temporal_layer";
+    if (!plan || !X || !W || !workspace || !Y) return fail(DSATTN_EINVAL, "%s: null argument", who);
+    if (plan->device < 0) return fail(DSATTN_ENODEVICE, "%s: host-only plan", who);
+    if (plan->desc.out_dtype != plan->desc.io_dtype)
+        return fail(DSATTN_EUNSUPPORTED, "%s: the plan's out_dtype must equal its io_dtype (the "
+                                         "attention's output is the output projection's input)", who);
+    const size_t slab = layer_slab_bytes(*plan);
+    if (workspace_bytes < 4 * slab)
+        return fail(DSATTN_EINVAL, "%s: workspace of %zu bytes, %zu needed", who, workspace_bytes,
+                    4 * slab);
+    if (misaligned(X) || misaligned(Y) || ((uintptr_t)workspace & 255u))
+        return fail(DSATTN_EINVAL, "%s: X and Y must be 16-byte and the workspace 256-byte aligned", who);
+    const size_t n = (size_t)plan->F * plan->desc.spatial * plan->C * dtype_size(plan->desc.io_dtype);
+    if (overlaps(workspace, 4 * slab, X, n) || overlaps(workspace, 4 * slab, Y, n))
+        return fail(DSATTN_EINVAL, "%s: the workspace overlaps X or Y", who);
+    if (X != Y && overlaps(X, n, Y, n))
+        return fail(DSATTN_EINVAL, "%s: Y overlaps X without being X", who);
+    unsigned char *ws = (unsigned char *)workspace;
+    void *q = ws, *k = ws + slab, *v = ws + 2 * slab, *o = ws + 3 * slab;
+    DeviceGuard g(plan->device);
+    if (g.err != hipSuccess) return hip_fail(g.err, "dsattn_temporal_layer: hipSetDevice");
+    dsattn_linear_desc l{};
+    l.rows = (int64_t)plan->F * plan->desc.spatial;
+    l.c_in = l.c_out = plan->C;
+    l.io_dtype = l.out_dtype = plan->desc.io_dtype;
+    l.flags = plan->desc.flags & DSATTN_FLAG_FORCE_GENERIC;
+    // stage 1: Q, K, V from the tokens, X read once
+    l.n_out = 3;
+    void *const qkv[3] = {q, k, v};
+    int rc = dsattn_linear(&l, X, W, bias, qkv, stream);
+    if (rc != DSATTN_OK) return rc;
+    // stage 2: Dual-scope attention
+    rc = dsattn_forward(plan, q, k, v, o, stream);
+    if (rc != DSATTN_OK) return rc;
+    // stage 3: output projection
+    l.n_out = 1;
+    const float *const bo = bias ? bias[3] : nullptr;
+    return dsattn_linear(&l, o, W + 3, bias ? &bo : nullptr, &Y, stream);
+}
+
 int dsattn_copy_probe(void *dst, const void *src, int64_t bytes, void *stream)
 {
     if (!dst || !src || bytes <= 0 || (bytes & 15) || misaligned(dst) || misaligned(src))

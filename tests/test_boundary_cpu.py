@@ -436,3 +436,28 @@ def test_wide_contexts_reach_the_matrix_core_kernel():
         assert i["kernel"] == kernel, (D, h, w, G, i)
         if tiles:
             assert (i["local_tiles"], i["global_tiles"]) == tiles, (D, h, w, G, i)
+
+
+def test_layer_entry_point_checks_its_arguments_on_the_host():
+    lib = B.load()
+    plan = B.dsattn_plan(16, 4, 2, 5, 8, 40, [0, 9], device=-1)
+    need = B.dsattn_temporal_layer_workspace(plan)
+    one = 64 * 5 * 320 * 2                                  # one [F, P, C] bf16 tensor
+    assert need == 4 * ((one + 255) // 256 * 256)
+    n = ctypes.c_size_t(0)
+    assert lib.dsattn_temporal_layer_workspace(None, ctypes.byref(n)) == B.DSATTN_EINVAL
+    assert lib.dsattn_temporal_layer_workspace(plan.handle, None) == B.DSATTN_EINVAL
+    w = (ctypes.c_void_p * 4)(0x100000, 0x200000, 0x300000, 0x400000)
+    args = lambda **kw: [kw.get("plan", plan.handle), kw.get("x", 0x1000000), kw.get("w", w), None,
+                         kw.get("ws", 0x8000000), kw.get("n", need), kw.get("y", 0x4000000), None]
+    assert lib.dsattn_temporal_layer(*args(plan=None)) == B.DSATTN_EINVAL
+    assert lib.dsattn_temporal_layer(*args(x=None)) == B.DSATTN_EINVAL
+    assert lib.dsattn_temporal_layer(*args(w=None)) == B.DSATTN_EINVAL
+    assert lib.dsattn_temporal_layer(*args(ws=None)) == B.DSATTN_EINVAL
+    assert lib.dsattn_temporal_layer(*args(y=None)) == B.DSATTN_EINVAL
+    assert lib.dsattn_temporal_layer(*args()) == B.DSATTN_ENODEVICE      # host-only plan
+    plan.close()
+    # fp32 output of bf16 attention cannot feed the output projection
+    plan = B.dsattn_plan(16, 4, 2, 5, 8, 40, [0, 9], out_dtype=B.DSATTN_F32, device=-1)
+    assert lib.dsattn_temporal_layer(*args(plan=plan.handle)) == B.DSATTN_ENODEVICE
+    plan.close()

@@ -370,6 +370,59 @@ def test_whole_temporal_attention_layer_stage_by_stage():
     assert np.sqrt((err ** 2).mean()) <= 4e-3
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("in_place,with_qkv_bias", [(False, False), (True, True)])
+def test_layer_entry_point_equals_its_three_stages(in_place, with_qkv_bias):
+    """dsattn_temporal_layer enqueues the same three launches as the separate calls: its result
+    and the workspace's Q, K, V, A are bit-identical to theirs, and the result meets the oracle
+    chain (with the oracle rounding to bf16 between its stages as the tensors do)."""
+    clip_len, n_clips, w, P, h, D = 16, 4, 2, 9, 8, 40
+    F, C = clip_len * n_clips, h * D
+    g = synth.stride_global_idx(F, 16).tolist()
+    print(f"[case] layer entry {n_clips}x{clip_len} frames P={P} {h}x{D} in_place={in_place}", flush=True)
+    x = synth.make_tensor(F, P, C, 51, "correlated", "bf16").to(DEV)
+    wb = [synth.make_conv_weights(1, C, C, 52 + k, "bf16") for k in range(4)]
+    ws = [t[0].reshape(C, C).to(DEV) for t in wb]
+    bs = [t[1].to(DEV) if (with_qkv_bias or k == 3) else None for k, t in enumerate(wb)]
+    plan = B.dsattn_plan(clip_len, n_clips, w, P, h, D, g, io_dtype=B.DSATTN_BF16, device=0)
+    # the separate calls
+    q, k, v, o, y = (torch.full_like(x, float("nan")) for _ in range(5))
+    B.dsattn_linear(F * P, C, C, x, ws[:3], [q, k, v], biases=bs[:3])
+    B.dsattn_forward(plan, q, k, v, o)
+    B.dsattn_linear(F * P, C, C, o, ws[3:], [y], biases=bs[3:])
+    # the one call, on a workspace with a little slack in front of the needed bytes
+    need = B.dsattn_temporal_layer_workspace(plan)
+    assert need >= 4 * x.numel() * 2 and need % 256 == 0
+    space = torch.full((need,), 0xFF, dtype=torch.uint8, device=DEV)
+    x2 = x.clone()
+    y2 = x2 if in_place else torch.full_like(x, float("nan"))
+    B.dsattn_temporal_layer(plan, x2, ws, space, y2, biases=bs)
+    torch.cuda.synchronize()
+    assert torch.equal(y2, y)
+    slab = need // 4
+    for i, (t, name) in enumerate(zip((q, k, v, o), "QKVA")):
+        got = space[i * slab: i * slab + t.numel() * 2].view(torch.bfloat16).reshape(t.shape)
+        assert torch.equal(got, t), name
+    # a short workspace, a misaligned one and one that overlaps Y are refused before any launch
+    with pytest.raises(B.DsattnError, match="workspace"):
+        B.dsattn_temporal_layer(plan, x, ws, space[: need - 256], y, biases=bs)
+    big = torch.empty(need + 256, dtype=torch.uint8, device=DEV)
+    with pytest.raises(B.DsattnError, match="aligned"):
+        B.dsattn_temporal_layer(plan, x, ws, big[16:], y, biases=bs)
+    with pytest.raises(B.DsattnError, match="overlaps"):
+        B.dsattn_temporal_layer(plan, x, ws, space, space[:x.numel() * 2].view(torch.bfloat16).reshape(x.shape),
+                                biases=bs)
+    plan.close()
+    f64 = lambda t: None if t is None else t.to("cpu").to(torch.float64).numpy()
+    rb = lambda a: torch.from_numpy(a).to(torch.bfloat16).to(torch.float64).numpy()
+    qo, ko, vo = (rb(oracle.linear(f64(x), f64(ws[i]), bias=f64(bs[i]))).reshape(F, P, h, D) for i in range(3))
+    oo = rb(oracle.forward(qo, ko, vo, clip_len, n_clips, w, g).reshape(F, P, C))
+    yo = oracle.linear(oo, f64(ws[3]), bias=f64(bs[3]))
+    err = np.abs(f64(y2) - yo)
+    assert err.max() <= 4e-2, err.max()
+    assert np.sqrt((err ** 2).mean()) <= 4e-3
+
+
 def test_conv_falls_back_when_offsets_would_not_fit_32_bits():
     # the matrix-core kernel addresses a tile's X rows and all of W with 32-bit byte offsets
     assert B.dsattn_temporal_conv_info(16, 4, 40000, 1280, 64, 16)["kernel"] == 0   # reach x P rows x c_in
