@@ -20,9 +20,11 @@
 // XOR-swizzled in 16-byte chunks, which keeps the operand reads free of bank conflicts.  The
 // matrix instructions, the LDS reads of the next fragments and the issue of the next stage's
 // loads are interleaved by hand.  Rows outside the video are zeroed by the buffer descriptor's
-// range check, not by code.  Workgroups are numbered so that each XCD walks a contiguous run of
-// tiles (all column tiles of a few neighbouring row tiles): the W slabs, and the X rows shared
-// between taps and column tiles, are then served by that XCD's L2.
+// range check, not by code.  The workgroups are persistent: at most one per compute unit, the
+// same number on every XCD, each walking its share of the output tiles as one continuous stream
+// of stages (the next tile's first stage is loading while the finished tile is stored).  An XCD
+// walks a contiguous run of tiles (all column tiles of a few neighbouring row tiles): the W
+// slabs, and the X rows shared between taps and column tiles, are then served by that XCD's L2.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 

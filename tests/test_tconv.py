@@ -423,6 +423,35 @@ def test_layer_entry_point_equals_its_three_stages(in_place, with_qkv_bias):
     assert np.sqrt((err ** 2).mean()) <= 4e-3
 
 
+@pytest.mark.gpu
+def test_layer_in_hip_graph_replays():
+    """After one eager call the layer is three kernel launches and nothing else: captured once,
+    every replay (with eager work and synchronisations in between) reproduces the eager result."""
+    clip_len, n_clips, w, P, h, D = 16, 3, 2, 5, 4, 80
+    F, C = clip_len * n_clips, h * D
+    g = [1, 17, 40]
+    print(f"[case] layer in a graph {n_clips}x{clip_len} frames P={P} {h}x{D}", flush=True)
+    x = synth.make_tensor(F, P, C, 61, "correlated", "bf16").to(DEV)
+    ws = [synth.make_conv_weights(1, C, C, 62 + k, "bf16")[0].reshape(C, C).to(DEV) for k in range(4)]
+    plan = B.dsattn_plan(clip_len, n_clips, w, P, h, D, g, io_dtype=B.DSATTN_BF16, device=0)
+    space = torch.zeros(B.dsattn_temporal_layer_workspace(plan), dtype=torch.uint8, device=DEV)
+    y_eager = torch.empty_like(x)
+    B.dsattn_temporal_layer(plan, x, ws, space, y_eager)
+    torch.cuda.synchronize()
+    y = torch.zeros_like(x)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.dsattn_temporal_layer(plan, x, ws, space, y)
+    for rep in range(3):
+        y.fill_(0)
+        space.fill_(0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_eager), f"replay {rep} differs from the eager result"
+    plan.close()
+
+
 def test_conv_falls_back_when_offsets_would_not_fit_32_bits():
     # the matrix-core kernel addresses a tile's X rows and all of W with 32-bit byte offsets
     assert B.dsattn_temporal_conv_info(16, 4, 40000, 1280, 64, 16)["kernel"] == 0   # reach x P rows x c_in
