@@ -124,3 +124,52 @@ def test_paper_sized_clips_on_a_slice_of_the_headline_tensor():
     # the headline level's row shape on a few positions
     info, *_ = run(288, 8, 8, 8, 16, 8, 160, 4, seed=800, out="bf16", gen="correlated")
     assert info["local_tiles"] == 2 and info["global_tiles"] == 1 and info["heads_per_wave"] == 1
+
+
+def test_randomised_options_against_oracle():
+    """Seeded sweep over the options together: clip lengths of one to four tiles, windows, both
+    scope biases, the set union, up to 128 global frames with repeats, both output types, and the
+    materialised-context path beside the fused one (identical bits expected)."""
+    rng = np.random.default_rng(77)
+    ran = {0: 0, 1: 0}
+    for case in range(40):
+        D = int(rng.choice([40, 80, 160, 64, 96]))
+        h = int(rng.choice([1, 2, 3, 4, 8]))
+        clip_len = int(rng.choice([16, 32, 48, 64]))
+        n_clips = int(rng.integers(1, 5))
+        F = clip_len * n_clips
+        w = int(rng.integers(0, 17))
+        G = int(rng.choice([0, 3, 16, 30, 64, 65, 128]))
+        g = rng.integers(0, F, size=G).tolist()
+        P = int(rng.integers(1, 5))
+        window = None if (clip_len == 16 and rng.random() < 0.5) else int(rng.integers(0, 17))
+        bl, bg = (0.0, 0.0) if rng.random() < 0.5 else (float(rng.normal()), float(rng.normal()))
+        dedup = bool(rng.random() < 0.3)
+        od = "f32" if rng.random() < 0.6 else "bf16"
+        scale = 0.0 if rng.random() < 0.7 else float(2.5 / np.sqrt(D))
+        print(f"[case] random options {case}: D={D} h={h} Fc={clip_len} N={n_clips} w={w} G={G} P={P} "
+              f"window={window} biases=({bl:.2f},{bg:.2f}) dedup={dedup} out={od} scale={scale:.3f}",
+              flush=True)
+        q, k, v = make(F, P, h * D, 2000 + case)
+        flags = B.DSATTN_FLAG_DEDUP_GLOBAL if dedup else 0
+        ref = U.oracle_forward(q, k, v, clip_len, n_clips, w, h, g, scale=scale, window=window,
+                               bias_local=bl, bias_global=bg, dedup=dedup)
+        plan = B.dsattn_plan(clip_len, n_clips, w, P, h, D, g, io_dtype=B.DSATTN_BF16,
+                             out_dtype=U.dt_code(od), scale=scale, flags=flags, device=0,
+                             bias_local=bl, bias_global=bg, window=window)
+        info = B.dsattn_plan_launch_info(plan)
+        ran[info["kernel"]] += 1
+        o1 = torch.full((F, P, h * D), float("nan"), dtype=synth.torch_dtype(od), device=DEV)
+        o2 = torch.full_like(o1, float("nan"))
+        B.dsattn_forward(plan, q, k, v, o1)
+        lk = B.dsattn_plan_ctx_max(plan)
+        kc = torch.empty((n_clips, lk, P, h * D), dtype=k.dtype, device=DEV)
+        vc = torch.empty_like(kc)
+        B.dsattn_gather_context(plan, k, v, kc, vc)
+        B.dsattn_forward_ctx(plan, q, kc, vc, o2)
+        torch.cuda.synchronize()
+        plan.close()
+        U.assert_parity(o1, ref, od, what=f"random options {case} (kernel {info['kernel']})")
+        assert torch.equal(o1.view(torch.int32 if od == "f32" else torch.int16),
+                           o2.view(torch.int32 if od == "f32" else torch.int16)), case
+    assert ran[0] >= 3 and ran[1] >= 15, ran   # the sweep reaches both kernels
