@@ -117,10 +117,14 @@ __device__ __forceinline__ float colmax(float x)
 
 // The multiply-accumulate of the accumulator chains of O^T = V^T P^T and of the denominator.  A
 // kernel variant takes its key tiles either in pairs (32 keys per 16x16x32 instruction) or one
-// by one (16 keys per 16x16x16 instruction), never both: a 16x16x16 result fed as the C operand
-// of a 16x16x32 issued right behind it came back with wrong elements on this toolchain.  Every
-// step of those chains goes through PvChain<kPairs>::mac, whose operand types fit one instruction
-// only, so a chain that mixes the two does not compile.
+// by one (16 keys per 16x16x16 instruction), never both.  The matrix cores hand an accumulator
+// from one instruction straight to the next only between instructions of the same shape; a
+// 16x16x32 that takes a 16x16x16's result as its C operand right behind it reads elements 2 and
+// 3 before they are written (the other way round: elements 0 and 1), and this toolchain puts no
+// wait state between the two.  Checked with a two-instruction probe on the device: no wait,
+// those elements stale in every lane; a few s_nop in between, or the same shape twice, correct.
+// Every step of those chains goes through PvChain<kPairs>::mac, whose operand types fit one
+// instruction only, so a chain that mixes the two does not compile.
 template <bool PAIRS>
 struct PvChain;
 template <>
