@@ -391,6 +391,16 @@ def main():
     wcat = torch.cat(proj_w, 0).contiguous()
     vendor_qkv_ms = timed(lambda: torch.matmul(L0["q"].view(rows, lvl.C), wcat.t()))
     vendor_one_ms = timed(lambda: torch.matmul(L0["q"].view(rows, lvl.C), wo.t()))
+    # the same two calls in alternation (the vendor's rate has been seen to rise during a process):
+    # three rounds of ten launches each, every round reported
+    vendor_y = torch.empty((rows, 3 * lvl.C), dtype=torch.bfloat16, device=dev)
+    rounds = []
+    for _ in range(3):
+        v_ms = timed(lambda: torch.matmul(L0["q"].view(rows, lvl.C), wcat.t(), out=vendor_y), reps=10)
+        o_ms = timed(proj, reps=10)
+        rounds.append({"vendor_TFLOPps": round(proj_info["useful_flops"] / v_ms / 1e9, 1),
+                       "dsattn_linear_TFLOPps": round(proj_info["useful_flops"] / o_ms / 1e9, 1)})
+    del vendor_y
     temporal_layer = {
         "entry_point": "dsattn_temporal_layer",
         "ms": round(layer_ms, 4),
@@ -404,7 +414,8 @@ def main():
             "qkv_as_one_gemm_ms": round(vendor_qkv_ms, 4),
             "qkv_as_one_gemm_TFLOPps": round(3 * proj_flops1 / vendor_qkv_ms / 1e9, 1),
             "one_projection_ms": round(vendor_one_ms, 4),
-            "one_projection_TFLOPps": round(proj_flops1 / vendor_one_ms / 1e9, 1)},
+            "one_projection_TFLOPps": round(proj_flops1 / vendor_one_ms / 1e9, 1),
+            "qkv_alternating_rounds": rounds},
     }
     del proj_w, proj_y, wo, yo, wcat, layer_space
     # ---- the other workloads, so that one run shows every level shape
